@@ -1,0 +1,74 @@
+// Host-side launch interface of the HIP kernels.  Every function only enqueues work on `st`.
+// dtype is PP_F32 (0) or PP_BF16 (1) and selects the storage type of "void*" activations/weights.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace pp {
+
+struct RowInfo {        // one packed row (d_model elements) of the trainable subset
+  int64_t canon_off;    // element offset of the row in the canonical params buffer
+  float wd_on;          // 1: weight decay applies, 0: norm gain
+  int32_t pad;
+};
+struct ShadowSeg {      // one trainable row block that also lives, transposed, in a shadow matrix
+  int64_t canon_off;    // element offset of the block's first element in params
+  int64_t shadow_off;   // element offset (from the shadow base) of its image: (r,c) -> shadow_off + c*shadow_ld + r
+  int32_t rows, cols, shadow_ld, tile_start;   // tile_start: first 64x64 tile index of this block in the batched launch
+};
+
+enum { EPI_STORE = 0, EPI_ADD_RES = 1 };
+
+void k_fill_f32(hipStream_t st, float* p, size_t n, float v);
+void k_rope_tables(hipStream_t st, float* cosb, float* sinb, int S, int dh, float base);
+void k_embed(hipStream_t st, int dtype, const int32_t* tok, const void* E, void* x, int T, int d, int V);
+void k_rmsnorm_fwd(hipStream_t st, int dtype, const void* x, const void* gamma, void* y, float* rstd, int T, int d, float eps);
+// dx = (dres ? dres : 0) + rmsnorm backward of dy ; dx may alias dres
+void k_rmsnorm_bwd(hipStream_t st, int dtype, const void* dy, const void* x, const float* rstd, const void* gamma,
+                   const void* dres, void* dx, int T, int d);
+// dgamma[c] = sum_t dy[t,c] * x[t,c] * rstd[t]; partial: float[64*d] scratch
+void k_rmsnorm_dgamma(hipStream_t st, int dtype, const void* dy, const void* x, const float* rstd, float* partial,
+                      float* dgamma, int T, int d);
+void k_rope(hipStream_t st, int dtype, void* qkv, const float* cosb, const float* sinb, int B, int S, int h, int dh, int inverse);
+void k_swiglu_fwd(hipStream_t st, int dtype, const void* gu, void* a, int T, int F);
+// dA: [T x (c1-c0)] with leading dimension ldA, holding columns c0..c1 of the activation gradient.
+void k_swiglu_bwd(hipStream_t st, int dtype, const void* gu, const void* dA, int ldA, void* dgu, int T, int F, int c0, int c1);
+void k_count_valid(hipStream_t st, const int32_t* targets, int T, int V, int32_t* n_valid);
+// logits [T x V] are overwritten with dL/dlogits; rowloss[T] gets the per-row loss (0 on ignored rows)
+int k_cross_entropy(hipStream_t st, int dtype, void* logits, const int32_t* targets, const int32_t* n_valid, float* rowloss, int T, int V);
+void k_loss_reduce(hipStream_t st, const float* rowloss, const int32_t* n_valid, float* loss, int T);
+void k_transpose(hipStream_t st, int dtype, const void* src, int ld_src, void* dst, int ld_dst, int rows, int cols);
+void k_shadow_refresh(hipStream_t st, int dtype, const void* params, void* shadow, const ShadowSeg* segs_dev, int n_segs, int n_tiles);
+
+// C[M x N] (ldc) = A[M x K] (lda) * B[N x K]^T (ldb)  [+ R[M x N] (ldc) if epi == EPI_ADD_RES]
+// out_f32: C is float regardless of dtype.  Plain (non-MFMA) kernel, any shape.
+void k_gemm_nt_plain(hipStream_t st, int dtype, const void* A, int lda, const void* B, int ldb, void* C, int ldc,
+                     int M, int N, int K, int epi, const void* R, int out_f32);
+// split-K variant: partial[z][M][N] float, z = 0..splits-1 over equal K chunks (K % splits == 0)
+void k_gemm_nt_plain_splitk(hipStream_t st, int dtype, const void* A, int lda, const void* B, int ldb, float* partial,
+                            int M, int N, int K, int splits);
+void k_splitk_reduce(hipStream_t st, const float* partial, float* C, int ldc, int M, int N, int splits);
+
+void k_attn_fwd_plain(hipStream_t st, int dtype, const void* qkv, void* o, float* lse, int B, int S, int h, int dh);
+void k_attn_D(hipStream_t st, int dtype, const void* o, const void* dO, float* Dbuf, int B, int S, int h, int dh);
+void k_attn_bwd_plain(hipStream_t st, int dtype, const void* qkv, const void* o, const float* lse, const void* dO, void* dqkv,
+                      float* Dbuf, int B, int S, int h, int dh);
+
+void k_embed_grad(hipStream_t st, int dtype, const int32_t* tok, const void* dx, float* gE, int T, int d, int V);
+
+void k_pack_master(hipStream_t st, int dtype, const void* params, const RowInfo* rows, float* p, int n_rows, int d);
+void k_adamw(hipStream_t st, int dtype, void* params, const RowInfo* rows, float* p, float* m, float* v, const float* g,
+             int n_rows, int d, float lr, float beta1, float beta2, float eps, float wd, float bc1, float bc2);
+void k_outer(hipStream_t st, int dtype, void* params, const RowInfo* rows, float* master, float* theta_g, float* mom,
+             const float* others, float* delta_out, int n_rows, int d, float lr, float mu, int nesterov, float inv_m);
+void k_synth_delta_sum(hipStream_t st, float* dst, size_t n, const uint64_t* keys_dev, int n_nodes, float std);
+
+// MFMA paths (bf16 only).  Return 0 if launched, 1 if the shape is not supported (caller falls back).
+int k_gemm_nt_mfma(hipStream_t st, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
+                   int epi, const void* R, int out_f32, int splits, float* partial);
+int k_attn_fwd_mfma(hipStream_t st, const void* qkv, void* o, float* lse, int B, int S, int h, int dh);
+int k_attn_bwd_mfma(hipStream_t st, const void* qkv, const void* o, const float* lse, const void* dO, void* dqkv, float* Dbuf,
+                    int B, int S, int h, int dh);
+
+}  // namespace pp

@@ -1,0 +1,40 @@
+/* pp_ops.h -- op-level entry points of the same library: the dense contractions of the local step, callable
+ * on their own so that each kernel can be checked against a plain definition and timed against its roofline.
+ * All pointers are device pointers owned by the caller; all calls only enqueue work on `hip_stream`.
+ * dtype: PP_F32 or PP_BF16 storage (see pp.h).  Return PP_OK or a negative PP_E* code (pp_last_error()).
+ */
+#ifndef PP_OPS_H
+#define PP_OPS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* C[M x N] = A[M x K] * B[N x K]^T (+ R[M x N] if R != NULL), row-major with leading dimensions lda, ldb, ldc
+ * (R uses ldc).  Every matmul of the forward pass and of the partial backward (Appendix "Partial Backward":
+ * dA = V_n^T G, dX = sum_n W_n^T dH_n, dW_n = dH_n X^T, dV_n = G A_n^T) is issued in this form.
+ * out_f32 != 0: C is float (weight gradients); then R must be NULL.
+ * splits > 1 (needs out_f32, scratch_dev of M*N*splits floats): K is cut into `splits` equal ranges whose
+ * partial products are summed in fixed order into C.
+ * path: 0 = automatic (MFMA kernel when dtype is bf16 and K % 64 == 0, lda % 8 == 0, ldb % 8 == 0), 1 = plain kernel. */
+int pp_op_gemm_nt(void* hip_stream, int dtype, const void* A_dev, int lda, const void* B_dev, int ldb, void* C_dev, int ldc,
+                  int M, int N, int K, const void* R_dev, int out_f32, int splits, float* scratch_dev, int path);
+
+/* Causal softmax attention (Appendix "MHA with frozen heads", forward of every head; mask from the autoregressive
+ * factorisation of Section 2.1).  qkv_dev: [B*S x 3*h*dh], columns q | k | v, head j at columns j*dh of each part
+ * (q and k already rotated).  o_dev: [B*S x h*dh].  lse_dev: float [B*h*S], log-sum-exp of the scaled scores.
+ * path as above. */
+int pp_op_attention_fwd(void* hip_stream, int dtype, const void* qkv_dev, void* o_dev, float* lse_dev, int B, int S, int h, int dh, int path);
+
+/* Backward of the above for all heads: dqkv_dev [B*S x 3*h*dh] receives dq | dk | dv (in the rotated frame);
+ * D_dev: float [B*h*S] scratch (row sums of dO * O). */
+int pp_op_attention_bwd(void* hip_stream, int dtype, const void* qkv_dev, const void* o_dev, const float* lse_dev, const void* dO_dev,
+                        void* dqkv_dev, float* D_dev, int B, int S, int h, int dh, int path);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PP_OPS_H */

@@ -14,7 +14,8 @@ import numpy as np
 PP_F32, PP_BF16 = 0, 1
 PP_BYTES_PARAMS, PP_BYTES_STATE, PP_BYTES_WORKSPACE, PP_BYTES_SHADOW, PP_BYTES_ACTIVATIONS = range(5)
 EXPORTS = ["pp_query_bytes", "pp_init_model", "pp_set_tensor", "pp_get_tensor", "pp_set_trainable_mask", "pp_local_step",
-           "pp_outer_delta", "pp_synth_delta_sum", "pp_get_counters", "pp_set_option", "pp_last_error", "pp_free"]
+           "pp_outer_delta", "pp_synth_delta_sum", "pp_get_counters", "pp_set_option", "pp_last_error", "pp_free",
+           "pp_op_gemm_nt", "pp_op_attention_fwd", "pp_op_attention_bwd"]
 
 
 class PPError(RuntimeError):
@@ -81,6 +82,12 @@ def load_library():
     lib.pp_last_error.argtypes = []
     lib.pp_free.restype = None
     lib.pp_free.argtypes = [vp]
+    lib.pp_op_gemm_nt.restype = C.c_int
+    lib.pp_op_gemm_nt.argtypes = [vp, C.c_int, vp, C.c_int, vp, C.c_int, vp, C.c_int, C.c_int, C.c_int, C.c_int, vp, C.c_int, C.c_int, vp, C.c_int]
+    lib.pp_op_attention_fwd.restype = C.c_int
+    lib.pp_op_attention_fwd.argtypes = [vp, C.c_int, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]
+    lib.pp_op_attention_bwd.restype = C.c_int
+    lib.pp_op_attention_bwd.argtypes = [vp, C.c_int, vp, vp, vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]
     _lib = lib
     return lib
 
@@ -153,6 +160,21 @@ def pp_set_option(h, key: str, value: int):
 
 def pp_free(h):
     load_library().pp_free(h)
+
+
+def pp_op_gemm_nt(stream: int, dtype: int, A_ptr, lda, B_ptr, ldb, C_ptr, ldc, M, N, K, R_ptr=None, out_f32=0, splits=1,
+                  scratch_ptr=None, path=0):
+    _check(load_library().pp_op_gemm_nt(stream, dtype, A_ptr, lda, B_ptr, ldb, C_ptr, ldc, M, N, K, R_ptr, out_f32, splits,
+                                        scratch_ptr, path), "pp_op_gemm_nt")
+
+
+def pp_op_attention_fwd(stream: int, dtype: int, qkv_ptr, o_ptr, lse_ptr, B, S, h, dh, path=0):
+    _check(load_library().pp_op_attention_fwd(stream, dtype, qkv_ptr, o_ptr, lse_ptr, B, S, h, dh, path), "pp_op_attention_fwd")
+
+
+def pp_op_attention_bwd(stream: int, dtype: int, qkv_ptr, o_ptr, lse_ptr, dO_ptr, dqkv_ptr, D_ptr, B, S, h, dh, path=0):
+    _check(load_library().pp_op_attention_bwd(stream, dtype, qkv_ptr, o_ptr, lse_ptr, dO_ptr, dqkv_ptr, D_ptr, B, S, h, dh, path),
+           "pp_op_attention_bwd")
 
 
 # --------------------------------------------------------------------------------------------- convenience holder

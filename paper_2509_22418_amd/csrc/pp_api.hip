@@ -645,3 +645,56 @@ extern "C" int pp_get_counters(pp_model* m, double* flops_fwd, double* flops_bwd
   if (n_trainable) *n_trainable = m->n_train;
   return PP_OK;
 }
+
+// ------------------------------------------------------------------------------------------------ op-level entry points
+#include "../../include/pp_ops.h"
+
+extern "C" int pp_op_gemm_nt(void* hip_stream, int dtype, const void* A, int lda, const void* B, int ldb, void* C, int ldc,
+                             int M, int N, int K, const void* R, int out_f32, int splits, float* scratch, int path) {
+  if (!A || !B || !C) return fail(PP_EINVAL, "pp_op_gemm_nt: NULL pointer");
+  if (dtype != PP_F32 && dtype != PP_BF16) return fail(PP_EINVAL, "pp_op_gemm_nt: bad dtype");
+  if (M < 1 || N < 1 || K < 1 || lda < K || ldb < K || ldc < N) return fail(PP_EINVAL, "pp_op_gemm_nt: bad shape or leading dimension");
+  if (splits < 1 || K % splits) return fail(PP_EINVAL, "pp_op_gemm_nt: K must be a multiple of splits");
+  if (splits > 1 && (!out_f32 || !scratch || R)) return fail(PP_EINVAL, "pp_op_gemm_nt: split-K needs out_f32, scratch and no residual");
+  if (out_f32 && R) return fail(PP_EINVAL, "pp_op_gemm_nt: residual with float output is not supported");
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int epi = R ? EPI_ADD_RES : EPI_STORE;
+  const bool f32out = out_f32 || dtype == PP_F32;
+  bool done = false;
+  if (path == 0 && dtype == PP_BF16)
+    done = k_gemm_nt_mfma(st, A, lda, B, ldb, C, ldc, M, N, K, epi, R, out_f32, splits, scratch) == 0;
+  if (!done) {
+    if (splits > 1) k_gemm_nt_plain_splitk(st, dtype, A, lda, B, ldb, scratch, M, N, K, splits);
+    else k_gemm_nt_plain(st, dtype, A, lda, B, ldb, C, ldc, M, N, K, epi, R, f32out ? 1 : 0);
+  }
+  if (splits > 1) k_splitk_reduce(st, scratch, (float*)C, ldc, M, N, splits);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(PP_EHIP, std::string("pp_op_gemm_nt: ") + hipGetErrorString(e));
+  return PP_OK;
+}
+
+static int check_attn(int dtype, int B, int S, int h, int dh) {
+  if (dtype != PP_F32 && dtype != PP_BF16) return fail(PP_EINVAL, "attention: bad dtype");
+  if (B < 1 || S < 1 || h < 1 || dh < 2 || dh % 2 || dh > 256 || S > 8192) return fail(PP_EINVAL, "attention: bad shape");
+  return PP_OK;
+}
+extern "C" int pp_op_attention_fwd(void* hip_stream, int dtype, const void* qkv, void* o, float* lse, int B, int S, int h, int dh, int path) {
+  if (!qkv || !o || !lse) return fail(PP_EINVAL, "pp_op_attention_fwd: NULL pointer");
+  if (int rc = check_attn(dtype, B, S, h, dh)) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (!(path == 0 && dtype == PP_BF16 && k_attn_fwd_mfma(st, qkv, o, lse, B, S, h, dh) == 0)) k_attn_fwd_plain(st, dtype, qkv, o, lse, B, S, h, dh);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(PP_EHIP, std::string("pp_op_attention_fwd: ") + hipGetErrorString(e));
+  return PP_OK;
+}
+extern "C" int pp_op_attention_bwd(void* hip_stream, int dtype, const void* qkv, const void* o, const float* lse, const void* dO,
+                                   void* dqkv, float* Dbuf, int B, int S, int h, int dh, int path) {
+  if (!qkv || !o || !lse || !dO || !dqkv || !Dbuf) return fail(PP_EINVAL, "pp_op_attention_bwd: NULL pointer");
+  if (int rc = check_attn(dtype, B, S, h, dh)) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (!(path == 0 && dtype == PP_BF16 && k_attn_bwd_mfma(st, qkv, o, lse, dO, dqkv, Dbuf, B, S, h, dh) == 0))
+    k_attn_bwd_plain(st, dtype, qkv, o, lse, dO, dqkv, Dbuf, B, S, h, dh);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(PP_EHIP, std::string("pp_op_attention_bwd: ") + hipGetErrorString(e));
+  return PP_OK;
+}

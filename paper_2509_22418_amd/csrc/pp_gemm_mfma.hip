@@ -1,5 +1,176 @@
-// bf16 MFMA GEMM (NT) for gfx950 -- placeholder until the tiled kernel lands: reports "unsupported".
+// bf16 MFMA GEMM for gfx950:  C[M x N] = A[M x K] * B[N x K]^T  (both operands K-contiguous), fp32 accumulate.
+//
+// Every dense contraction of the local step is brought into this one form (forward projections use the weights
+// as stored, input-gradient GEMMs use transposed read-only weight copies, weight-gradient GEMMs use transposed
+// activations with the token dimension as K), so this is the kernel that carries the step's FLOPs.
+//
+// Tiling: 256 x 256 output tile per workgroup of 512 threads = 8 wavefronts (2 per SIMD) arranged 2 (M) x 4 (N);
+// each wavefront owns 128 x 64 = 4 x 2 MFMA tiles of v_mfma_f32_32x32x16_bf16 (128 accumulator registers).
+// K advances in steps of 64: the A and B panels (256 x 64 bf16 each, 32 KB + 32 KB) are staged in LDS, two stages
+// (128 KB of the CU's 160 KB), global loads for step k+1 are in flight in registers while step k is multiplied.
+// LDS rows are 128 bytes = 8 chunks of 16 bytes; chunk c of row r is stored at chunk c ^ (r & 7) so that the
+// 16-byte fragment reads of 8 consecutive rows fall into distinct banks.
+// Workgroup ids are remapped so that the workgroups resident on one XCD (ids equal mod 8) work on neighbouring
+// tiles (shared A / B panels hit that XCD's L2), in groups of 8 M-tiles by all N-tiles.
 #include "pp_kernels.h"
+#include "pp_dev.h"
+
 namespace pp {
-int k_gemm_nt_mfma(hipStream_t, const void*, int, const void*, int, void*, int, int, int, int, int, const void*, int, int, float*) { return 1; }
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int STAGE_CHUNKS = (BM + BN) * 8;          // 16-byte chunks per stage
+constexpr int GEMM_LDS_BYTES = 2 * STAGE_CHUNKS * 16;
+
+template <int EPI, bool OUT_F32>
+__global__ __launch_bounds__(512) void gemm_nt_mfma_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ B, int ldb,
+                                                            void* Cv, int ldc, int M, int N, int Ksplit, const bf16_t* __restrict__ R,
+                                                            int tiles_m, int tiles_n) {
+  extern __shared__ uint4 lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 2, wn = wave & 3;
+
+  // ---- tile assignment (XCD-aware remap, then grouped ordering)
+  const int nb = tiles_m * tiles_n;
+  int pid = blockIdx.x;
+  if ((nb & 7) == 0) pid = (pid & 7) * (nb >> 3) + (pid >> 3);
+  constexpr int GROUP = 8;
+  const int per_group = GROUP * tiles_n;
+  const int group = pid / per_group;
+  const int first_m = group * GROUP;
+  const int gsz = min(tiles_m - first_m, GROUP);
+  const int in_group = pid - group * per_group;
+  const int tm = first_m + in_group % gsz, tn = in_group / gsz;
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int z = blockIdx.y;
+  const size_t kbase = (size_t)z * Ksplit;
+
+  // ---- global -> register -> LDS staging: each thread moves 4 chunks of A and 4 chunks of B per K step
+  const int lrow = tid >> 3, lc = tid & 7;
+  const bf16_t* gA[4];
+  const bf16_t* gB[4];
+  int sOff[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = lrow + 64 * i;
+    gA[i] = A + (size_t)min(m0 + row, M - 1) * lda + kbase + lc * 8;
+    gB[i] = B + (size_t)min(n0 + row, N - 1) * ldb + kbase + lc * 8;
+    sOff[i] = row * 8 + (lc ^ (row & 7));
+  }
+  uint4 ra[4], rb[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { ra[i] = *reinterpret_cast<const uint4*>(gA[i]); rb[i] = *reinterpret_cast<const uint4*>(gB[i]); }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { lds[sOff[i]] = ra[i]; lds[BM * 8 + sOff[i]] = rb[i]; }
+  __syncthreads();
+
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int l32 = lane & 31, lhi = lane >> 5, sw = lane & 7;
+  const int aRow = (wm * 128 + l32) * 8, bRow = BM * 8 + (wn * 64 + l32) * 8;
+  const int nk = Ksplit / BK;
+  for (int kt = 0; kt < nk; ++kt) {
+    const int cur = (kt & 1) * STAGE_CHUNKS, nxt = ((kt + 1) & 1) * STAGE_CHUNKS;
+    const bool more = kt + 1 < nk;
+    if (more) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        ra[i] = *reinterpret_cast<const uint4*>(gA[i] + (size_t)(kt + 1) * BK);
+        rb[i] = *reinterpret_cast<const uint4*>(gB[i] + (size_t)(kt + 1) * BK);
+      }
+    }
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int pc = (2 * s + lhi) ^ sw;
+      bf16x8 af[4], bfr[2];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) af[i] = __builtin_bit_cast(bf16x8, lds[cur + aRow + i * 32 * 8 + pc]);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) bfr[j] = __builtin_bit_cast(bf16x8, lds[cur + bRow + j * 32 * 8 + pc]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+    if (more) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { lds[nxt + sOff[i]] = ra[i]; lds[nxt + BM * 8 + sOff[i]] = rb[i]; }
+    }
+    __syncthreads();
+  }
+
+  // ---- epilogue: accumulator element r of MFMA tile (i, j) is row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
+  const int col_base = n0 + wn * 64 + l32;
+  const int row_base = m0 + wm * 128 + 4 * lhi;
+  if constexpr (OUT_F32) {
+    float* C = reinterpret_cast<float*>(Cv) + (size_t)z * (size_t)M * (size_t)ldc;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int col = col_base + j * 32;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
+          if (row < M && col < N) C[(size_t)row * ldc + col] = acc[i][j][r];
+        }
+      }
+  } else {
+    bf16_t* C = reinterpret_cast<bf16_t*>(Cv);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int col = col_base + j * 32;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
+          if (row < M && col < N) {
+            float v = acc[i][j][r];
+            if constexpr (EPI == EPI_ADD_RES) v += to_f32(R[(size_t)row * ldc + col]);
+            C[(size_t)row * ldc + col] = from_f32<bf16_t>(v);
+          }
+        }
+      }
+  }
 }
+
+template <int EPI, bool OUT_F32>
+static int launch(hipStream_t st, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int Ksplit, const void* R, int splits) {
+  static bool attr_done = false;          // one-time opt-in to > 64 KB of dynamic LDS for this instantiation
+  auto kern = gemm_nt_mfma_kernel<EPI, OUT_F32>;
+  if (!attr_done) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES) != hipSuccess) return 1;
+    attr_done = true;
+  }
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  dim3 grid(tiles_m * tiles_n, splits);
+  kern<<<grid, 512, GEMM_LDS_BYTES, st>>>((const bf16_t*)A, lda, (const bf16_t*)B, ldb, C, ldc, M, N, Ksplit, (const bf16_t*)R, tiles_m, tiles_n);
+  return 0;
+}
+
+// splits > 1: `partial` receives [splits][M][N] fp32 (C is ignored); splits == 1 writes C directly.
+int k_gemm_nt_mfma(hipStream_t st, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
+                   int epi, const void* R, int out_f32, int splits, float* partial) {
+  if (M < 1 || N < 1 || splits < 1 || K % splits) return 1;
+  const int Ksplit = K / splits;
+  if (Ksplit < BK || Ksplit % BK || lda % 8 || ldb % 8) return 1;
+  if (((uintptr_t)A | (uintptr_t)B) & 15) return 1;
+  if (splits > 1) {
+    if (!out_f32 || !partial || epi != EPI_STORE) return 1;
+    return launch<EPI_STORE, true>(st, A, lda, B, ldb, partial, N, M, N, Ksplit, nullptr, splits);
+  }
+  if (out_f32) return epi == EPI_STORE ? launch<EPI_STORE, true>(st, A, lda, B, ldb, C, ldc, M, N, Ksplit, nullptr, 1) : 1;
+  if (epi == EPI_ADD_RES) return launch<EPI_ADD_RES, false>(st, A, lda, B, ldb, C, ldc, M, N, Ksplit, R, 1);
+  return launch<EPI_STORE, false>(st, A, lda, B, ldb, C, ldc, M, N, Ksplit, nullptr, 1);
+}
+
+}  // namespace pp

@@ -12,7 +12,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "pp.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", f)).read() for f in sorted(os.listdir(os.path.join(ROOT, "include"))))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(pp_[a-z_]+)\s*\(", text)))
 
@@ -30,7 +30,7 @@ def test_query_bytes_and_argument_checks_without_gpu():
     from paper_2509_22418_amd import binding as b
     cfg = gen.make_config("1p3b")
     c = b.make_config(cfg)
-    P = sum(a * (bb if len((a, bb)) else 1) for a, bb in [(s[0], s[1] if len(s) == 2 else 1) for s in gen.tensor_shapes(cfg).values()])
+    P = sum(s[0] * (s[1] if len(s) == 2 else 1) for s in gen.tensor_shapes(cfg).values())
     assert b.pp_query_bytes(c, None, b.PP_BYTES_PARAMS) == 2 * P
     m32 = b.make_mask(gen.ffn_slice_mask(cfg, 0, 32))
     m8 = b.make_mask(gen.ffn_slice_mask(cfg, 0, 8))

@@ -1,0 +1,127 @@
+"""Op-level parity of the dense-contraction kernels against their plain definitions (numpy fp64 on the same
+bf16-rounded inputs): the MFMA GEMM in all the forms the local step uses, and causal attention fwd/bwd."""
+import numpy as np
+import pytest
+import torch
+
+import pp_inputs as gen
+import paper_2509_22418_amd as pp
+from oracle import pp_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+def dev_bf16(x):
+    """numpy float array -> (device uint16 tensor of bf16 bits, float64 array of the rounded values)."""
+    r = gen.round_to_bf16(x)
+    return torch.from_numpy(gen.bf16_bits(r).astype(np.int16)).cuda(), r.astype(np.float64)
+
+
+def from_bf16(t):
+    return gen.bf16_bits_to_f32(t.cpu().numpy().view(np.uint16)).astype(np.float64)
+
+
+def rnd(shape, seed, std=1.0):
+    return gen.normal(gen.stream_key(seed, gen.STREAM_MISC, 0), int(np.prod(shape)), std).reshape(shape)
+
+
+GEMM_CASES = [
+    # M, N, K, residual, out_f32, splits
+    (512, 512, 256, False, False, 1),        # 2x2 tiles
+    (300, 200, 128, True, False, 1),         # ragged M and N inside one tile
+    (777, 1000, 192, False, False, 1),       # several tiles with ragged tails
+    (256, 768, 2048, True, False, 1),        # long K
+    (512, 256, 4096, False, True, 8),        # weight-gradient form: few tiles, split K, fp32 out
+    (128, 320, 1024, False, True, 1),
+    (64, 64, 100, False, False, 1),          # K not a multiple of 64: plain path
+]
+
+
+@pytest.mark.parametrize("M,N,K,res,f32,splits", GEMM_CASES)
+def test_gemm_nt_matches_definition(M, N, K, res, f32, splits):
+    print(f"case gemm {M}x{N}x{K} res={res} f32={f32} splits={splits}", flush=True)
+    Ad, A = dev_bf16(rnd((M, K), 1))
+    Bd, B = dev_bf16(rnd((N, K), 2))
+    ref = A @ B.T
+    st = torch.cuda.current_stream().cuda_stream
+    Rd = None
+    if res:
+        Rd, R = dev_bf16(rnd((M, N), 3, std=4.0))
+        ref = ref + R
+    scale = np.sqrt(K)
+    for path in (0, 1):
+        if f32:
+            Cd = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+            scratch = torch.empty(M * N * splits, dtype=torch.float32, device="cuda") if splits > 1 else None
+            pp.pp_op_gemm_nt(st, pp.PP_BF16, Ad.data_ptr(), K, Bd.data_ptr(), K, Cd.data_ptr(), N, M, N, K, None, 1, splits,
+                             None if scratch is None else scratch.data_ptr(), path)
+            torch.cuda.synchronize()
+            got = Cd.cpu().numpy().astype(np.float64)
+            assert np.max(np.abs(got - ref)) <= 2e-5 * scale * 4, (path, np.max(np.abs(got - ref)))
+        else:
+            Cd = torch.zeros((M, N), dtype=torch.int16, device="cuda")
+            pp.pp_op_gemm_nt(st, pp.PP_BF16, Ad.data_ptr(), K, Bd.data_ptr(), K, Cd.data_ptr(), N, M, N, K,
+                             None if Rd is None else Rd.data_ptr(), 0, 1, None, path)
+            torch.cuda.synchronize()
+            got = from_bf16(Cd)
+            # one bf16 rounding of the exact result: relative 2^-8, plus fp32 accumulation noise
+            assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-4 * scale), (path, np.max(np.abs(got - ref)))
+
+
+def test_gemm_with_leading_dimensions_and_column_slices():
+    """Operands and result addressed inside wider matrices (how slices of weights / activations are passed)."""
+    M, N, K, lda, ldb, ldc = 384, 320, 256, 512, 640, 1024
+    Ad, A = dev_bf16(rnd((M, lda), 4))
+    Bd, B = dev_bf16(rnd((N, ldb), 5))
+    Cd = torch.zeros((M, ldc), dtype=torch.int16, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    a_off, b_off, c_off = 64, 128, 256
+    pp.pp_op_gemm_nt(st, pp.PP_BF16, Ad.data_ptr() + 2 * a_off, lda, Bd.data_ptr() + 2 * b_off, ldb, Cd.data_ptr() + 2 * c_off, ldc,
+                     M, N, K, None, 0, 1, None, 0)
+    torch.cuda.synchronize()
+    got = from_bf16(Cd)
+    ref = A[:, a_off:a_off + K] @ B[:, b_off:b_off + K].T
+    assert np.all(np.abs(got[:, c_off:c_off + N] - ref) <= 2.0 ** -8 * np.abs(ref) + 2e-3)
+    assert np.all(got[:, :c_off] == 0) and np.all(got[:, c_off + N:] == 0)          # nothing written outside the slice
+
+
+ATTN_CASES = [(2, 128, 2, 128), (1, 256, 3, 64), (2, 200, 2, 128), (1, 77, 2, 64), (1, 512, 1, 128), (2, 64, 4, 16)]
+
+
+@pytest.mark.parametrize("B,S,h,dh", ATTN_CASES)
+def test_attention_fwd_bwd_matches_definition(B, S, h, dh):
+    print(f"case attention B={B} S={S} h={h} dh={dh}", flush=True)
+    d = h * dh
+    T = B * S
+    qkv_d, qkv = dev_bf16(rnd((T, 3 * d), 6))
+    dO_d, dO = dev_bf16(rnd((T, d), 7))
+    q = qkv[:, :d].reshape(B, S, h, dh)
+    k = qkv[:, d:2 * d].reshape(B, S, h, dh)
+    v = qkv[:, 2 * d:].reshape(B, S, h, dh)
+    o_ref, P = O.attention_fwd(q, k, v)
+    dq, dk, dv = O.attention_bwd(dO.reshape(B, S, h, dh), q, k, v, P)
+    dqkv_ref = np.concatenate([dq.reshape(T, d), dk.reshape(T, d), dv.reshape(T, d)], axis=1)
+    st = torch.cuda.current_stream().cuda_stream
+    for path in (0, 1):
+        o_d = torch.zeros((T, d), dtype=torch.int16, device="cuda")
+        lse_d = torch.zeros(B * h * S, dtype=torch.float32, device="cuda")
+        D_d = torch.zeros(B * h * S, dtype=torch.float32, device="cuda")
+        dqkv_d = torch.zeros((T, 3 * d), dtype=torch.int16, device="cuda")
+        pp.pp_op_attention_fwd(st, pp.PP_BF16, qkv_d.data_ptr(), o_d.data_ptr(), lse_d.data_ptr(), B, S, h, dh, path)
+        pp.pp_op_attention_bwd(st, pp.PP_BF16, qkv_d.data_ptr(), o_d.data_ptr(), lse_d.data_ptr(), dO_d.data_ptr(), dqkv_d.data_ptr(),
+                               D_d.data_ptr(), B, S, h, dh, path)
+        torch.cuda.synchronize()
+        o = from_bf16(o_d)
+        err = np.max(np.abs(o - o_ref.reshape(T, d)))
+        assert err <= 2e-2, (path, err)
+        got = from_bf16(dqkv_d)
+        for part, name in enumerate(("dq", "dk", "dv")):
+            a, b = got[:, part * d:(part + 1) * d], dqkv_ref[:, part * d:(part + 1) * d]
+            cos = float((a * b).sum() / (np.linalg.norm(a) * np.linalg.norm(b)))
+            assert cos >= 0.9995, (path, name, cos)
+            assert np.max(np.abs(a - b)) <= 0.03 * np.max(np.abs(b)), (path, name)
+        # log-sum-exp against the definition
+        s = np.einsum("bihc,bjhc->bhij", q, k) / np.sqrt(dh)
+        s = np.where(np.tril(np.ones((S, S), bool)), s, -np.inf)
+        lse_ref = np.log(np.exp(s - s.max(-1, keepdims=True)).sum(-1)) + s.max(-1)
+        assert np.max(np.abs(lse_d.cpu().numpy().reshape(B, h, S) - lse_ref)) <= 2e-3

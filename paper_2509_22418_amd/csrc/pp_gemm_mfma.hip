@@ -19,6 +19,7 @@ namespace pp {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int STAGE_CHUNKS = (BM + BN) * 8;          // 16-byte chunks per stage
@@ -28,7 +29,7 @@ template <int EPI, bool OUT_F32>
 __global__ __launch_bounds__(512) void gemm_nt_mfma_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ B, int ldb,
                                                             void* Cv, int ldc, int M, int N, int Ksplit, const bf16_t* __restrict__ R,
                                                             int tiles_m, int tiles_n) {
-  extern __shared__ uint4 lds[];
+  extern __shared__ u32x4 lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 2, wn = wave & 3;
 
@@ -59,9 +60,9 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_kernel(const bf16_t* __restr
     gB[i] = B + (size_t)min(n0 + row, N - 1) * ldb + kbase + lc * 8;
     sOff[i] = row * 8 + (lc ^ (row & 7));
   }
-  uint4 ra[4], rb[4];
+  u32x4 ra[4], rb[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) { ra[i] = *reinterpret_cast<const uint4*>(gA[i]); rb[i] = *reinterpret_cast<const uint4*>(gB[i]); }
+  for (int i = 0; i < 4; ++i) { ra[i] = *reinterpret_cast<const u32x4*>(gA[i]); rb[i] = *reinterpret_cast<const u32x4*>(gB[i]); }
 #pragma unroll
   for (int i = 0; i < 4; ++i) { lds[sOff[i]] = ra[i]; lds[BM * 8 + sOff[i]] = rb[i]; }
   __syncthreads();
@@ -79,14 +80,15 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_kernel(const bf16_t* __restr
   const int nk = Ksplit / BK;
   for (int kt = 0; kt < nk; ++kt) {
     const int cur = (kt & 1) * STAGE_CHUNKS, nxt = ((kt + 1) & 1) * STAGE_CHUNKS;
-    const bool more = kt + 1 < nk;
-    if (more) {
+    // prefetch the next K step into registers (the last iteration re-reads its own step; the copy it then
+    // stores lands in the stage nobody reads again)
+    const size_t knext = (size_t)min(kt + 1, nk - 1) * BK;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        ra[i] = *reinterpret_cast<const uint4*>(gA[i] + (size_t)(kt + 1) * BK);
-        rb[i] = *reinterpret_cast<const uint4*>(gB[i] + (size_t)(kt + 1) * BK);
-      }
+    for (int i = 0; i < 4; ++i) {
+      ra[i] = *reinterpret_cast<const u32x4*>(gA[i] + knext);
+      rb[i] = *reinterpret_cast<const u32x4*>(gB[i] + knext);
     }
+    __builtin_amdgcn_sched_barrier(0);          // keep the prefetch ahead of the multiply phase
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       const int pc = (2 * s + lhi) ^ sw;
@@ -100,10 +102,9 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_kernel(const bf16_t* __restr
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
-    if (more) {
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) { lds[nxt + sOff[i]] = ra[i]; lds[nxt + BM * 8 + sOff[i]] = rb[i]; }
-    }
+    for (int i = 0; i < 4; ++i) { lds[nxt + sOff[i]] = ra[i]; lds[nxt + BM * 8 + sOff[i]] = rb[i]; }
     __syncthreads();
   }
 

@@ -1,0 +1,197 @@
+#!/usr/bin/env python3
+"""Benchmark of the partial-parameter-update local step on one MI355X.
+
+A step = one pass of the whole hot path (forward over all parameters, restricted backward, AdamW on the
+trainable subset, write-back) over one batch of seeded synthetic tokens that already sit in HBM.
+Workload: the 1.3B-shape decoder (24 x 2048, 16 heads of 128, SwiGLU d_ff 8192, vocab 32000), batch 8 x 2048
+tokens, trainable subset = a contiguous 1/32 slice of every layer's FFN hidden units.  The same run also times the
+1/8 slice and the all-parameters-trainable (full back-propagation) step from the same library as the comparison
+legs, and the CPU fp64 oracle on a bounded sample.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HP = dict(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+PEAK_BF16_TFLOPS = 2500.0          # MI355X dense bf16 MFMA
+PEAK_HBM_GBPS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def closed_form_flops(cfg, B, S, rho):
+    """Executed matmul FLOPs per step for the FFN-slice mask (rho < 1) or the all-trainable step (rho = 1):
+    forward L(8Td^2 + 4 P d + 6TdF) + 2TdV, P = causal pairs; backward per the mask."""
+    T = B * S
+    d, L, F, V = cfg["d_model"], cfg["n_layers"], cfg["d_ff"], cfg["vocab"]
+    P = B * S * (S + 1) // 2
+    fwd = L * (8 * T * d * d + 4 * P * d + 6 * T * d * F) + 2 * T * d * V
+    if rho >= 1:
+        return fwd, 2 * fwd
+    Fk = F // round(1 / rho)
+    bwd = (2 * T * d * V + L * 6 * T * d * Fk + (L - 1) * 2 * T * d * F + 2 * T * d * Fk + (L - 1) * 4 * T * d * F
+           + (L - 1) * (8 * T * d * d + 8 * P * d))
+    return fwd, bwd
+
+
+def run_leg(torch, pp, gen, cfg, weights, mask, batches, steps, warmup, time_gemm):
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    torch.cuda.reset_peak_memory_stats()
+    m = pp.LocalStepModel(cfg, mask)
+    m.load_weights(weights)
+    m.set_mask()
+    dev = [m.upload_tokens(t, g) for t, g in batches]
+    for i in range(warmup):
+        m.step(*dev[i % len(dev)], HP)
+    torch.cuda.synchronize()
+    if time_gemm:
+        m.set_option("time_gemm", 1)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        m.step(*dev[i % len(dev)], HP)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    loss = float(m.loss.item())
+    gt = m.gemm_timing() if time_gemm else None
+    if time_gemm:
+        m.set_option("time_gemm", 0)
+    cnt = m.counters()
+    mem = m.memory_report()
+    peak_alloc = torch.cuda.max_memory_allocated()
+    m.close()
+    del m
+    return dict(seconds=dt, loss=loss, gemm=gt, counters=cnt, memory=mem, peak_alloc=peak_alloc)
+
+
+def cpu_baseline(gen, cfg, weights, seed):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload: full width (d, heads, d_ff, vocab),
+    first 2 of the layers, one sequence of 512 tokens, 1/32 FFN slice; one forward + restricted backward + AdamW."""
+    import numpy as np
+    from oracle import pp_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    L_s, B_s, S_s = 2, 1, 512
+    scfg = dict(cfg, n_layers=L_s)
+    keep = {k: v for k, v in weights.items() if not k.startswith("layers.") or int(k.split(".")[1]) < L_s}
+    mask = gen.ffn_slice_mask(scfg, 0, 32)
+    tok, tgt = gen.make_tokens(scfg, seed, step=0, batch=B_s, seq=S_s)
+    tr = O.LocalTrainer(scfg, keep, mask)
+    t0 = time.perf_counter()
+    loss, _ = tr.step(tok, tgt, HP, restricted=True)
+    dt = time.perf_counter() - t0
+    f_s = sum(closed_form_flops(scfg, B_s, S_s, 1 / 32))
+    f_full = sum(closed_form_flops(cfg, cfg["batch"], cfg["seq"], 1 / 32))
+    tok_s_sample = B_s * S_s / dt
+    # scale by FLOPs per token: the full workload has 24 layers and 2048-token sequences
+    per_tok_s = f_s / (B_s * S_s)
+    per_tok_full = f_full / (cfg["batch"] * cfg["seq"])
+    value = tok_s_sample * per_tok_s / per_tok_full
+    return dict(value=round(value, 3), unit="tokens/s", cores=int(cores), kind="oracle",
+                sample=f"fp64 numpy oracle, full width, {L_s} of {cfg['n_layers']} layers, B={B_s} S={S_s}, rho=1/32: "
+                       f"{dt:.2f} s for {B_s * S_s} tokens ({f_s / dt / 1e9:.1f} GFLOP/s fp64); value = sample tokens/s scaled "
+                       f"by FLOPs/token ({per_tok_s / 1e9:.2f} -> {per_tok_full / 1e9:.2f} GFLOP/token)",
+                seconds=round(dt, 3), loss=round(float(loss), 5))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="1p3b", choices=["1p3b", "125m"])
+    ap.add_argument("--legs", default="all", help="'main' = only the headline mask; 'all' = also rho=1/8 and all-trainable")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=1234)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs one node's local step on ONE GPU (no collectives exist in it); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import pp_inputs as gen
+    import paper_2509_22418_amd as pp
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    cfg = gen.make_config(args.workload)
+    B, S = cfg["batch"], cfg["seq"]
+    n_slices = cfg["n_slices"]
+    t0 = time.perf_counter()
+    weights = gen.make_weights(cfg, args.seed, threads=16)
+    log(f"[bench] weights generated in {time.perf_counter() - t0:.1f} s")
+    batches = [gen.make_tokens(cfg, args.seed, step=i) for i in range(4)]
+
+    legs = [("rho=1/%d" % n_slices, gen.ffn_slice_mask(cfg, 0, n_slices), 1.0 / n_slices)]
+    if args.legs == "all":
+        legs.append(("rho=1/8", gen.ffn_slice_mask(cfg, 0, 8), 1.0 / 8))
+        legs.append(("all-trainable", dict(all=1), 1.0))
+        if n_slices == 8:
+            legs.pop(1)
+    results = {}
+    for name, mask, rho in legs:
+        t1 = time.perf_counter()
+        r = run_leg(torch, pp, gen, cfg, weights, mask, batches, args.steps, args.warmup, time_gemm=True)
+        fwd, bwd = closed_form_flops(cfg, B, S, rho)
+        ms = r["seconds"] / args.steps * 1e3
+        executed = r["counters"]["flops_fwd"] + r["counters"]["flops_bwd"]
+        results[name] = dict(
+            tokens_per_s=round(B * S * args.steps / r["seconds"], 1), ms_per_step=round(ms, 3),
+            flops_executed=executed, flops_closed_form=fwd + bwd, flops_match=bool(executed == fwd + bwd),
+            step_tflops=round((fwd + bwd) / (ms * 1e-3) / 1e12, 1),
+            step_mfma_frac=round((fwd + bwd) / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+            gemm_tflops=round(r["gemm"]["flops"] / (r["gemm"]["ms"] * 1e-3) / 1e12, 1) if r["gemm"]["ms"] > 0 else None,
+            gemm_ms_per_step=round(r["gemm"]["ms"] / args.steps, 3), gemm_launches_per_step=r["gemm"]["launches"] // args.steps,
+            n_trainable=r["counters"]["n_trainable"], adamw_bytes=r["counters"]["adamw_bytes"],
+            hbm_bytes=r["memory"], peak_allocated_gb=round(r["peak_alloc"] / 2 ** 30, 3), final_loss=round(r["loss"], 5))
+        log(f"[bench] leg {name}: {results[name]['tokens_per_s']} tokens/s, {ms:.2f} ms/step, "
+            f"{results[name]['step_tflops']} TFLOP/s on executed FLOPs, GEMM {results[name]['gemm_tflops']} TFLOP/s "
+            f"({time.perf_counter() - t1:.1f} s incl. setup)")
+
+    main_name = legs[0][0]
+    mr = results[main_name]
+    gemm_ms_launch = mr["gemm_ms_per_step"] / max(mr["gemm_launches_per_step"], 1)
+    roofline = dict(bound="mfma", kernel="gemm_nt_mfma_kernel (all forward / dX / dW GEMM launches of the step)",
+                    achieved=mr["gemm_tflops"], peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                    frac=round(mr["gemm_tflops"] / PEAK_BF16_TFLOPS, 4) if mr["gemm_tflops"] else None, traffic=None,
+                    avg_launch_ms=round(gemm_ms_launch, 4), launches_per_step=mr["gemm_launches_per_step"],
+                    gemm_share_of_step_time=round(mr["gemm_ms_per_step"] / mr["ms_per_step"], 3))
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(gen, cfg, weights, args.seed)
+        log(f"[bench] cpu oracle: {cpu['value']} tokens/s on {cpu['cores']} threads")
+
+    out = {
+        "metric": "local-step tokens/s at 1.3B shape on 1 GPU" if args.workload == "1p3b" else "local-step tokens/s at 125M shape on 1 GPU",
+        "value": mr["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": mr["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}-shape decoder, {cfg['n_layers']}x{cfg['d_model']}, {cfg['n_heads']} heads, d_ff {cfg['d_ff']}, "
+                               f"vocab {cfg['vocab']}, batch {B} x seq {S}, trainable = 1/{n_slices} FFN slice per layer (partial update), "
+                               "Zipf(1.1) tokens, N(0,0.02) weights",
+                   "global_batch": B, "seq_len": S, "trainable_fraction_of_ffn": f"1/{n_slices}"},
+        "step_mfma_frac": mr["step_mfma_frac"], "peak_hbm_gb": mr["peak_allocated_gb"],
+        "roofline": roofline, "cpu_baseline": cpu, "legs": results,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -134,9 +134,15 @@ int pp_synth_delta_sum(pp_model* m, float* dst_dev, size_t n, const uint64_t* ke
  * bytes moved, and the number of trainable elements. */
 int pp_get_counters(pp_model* m, double* flops_fwd, double* flops_bwd, double* adamw_bytes, int64_t* n_trainable);
 
-/* Kernel-path selection for tests and profiling: 0 = automatic (MFMA kernels when shapes allow),
- * 1 = force the plain (non-MFMA) kernels. */
+/* Options for tests and profiling.  "force_plain": 0 = automatic (MFMA kernels when shapes allow), 1 = force the
+ * plain (non-MFMA) kernels.  "time_gemm": 1 = bracket every GEMM launch of later pp_local_step calls with a pair
+ * of HIP events on the model's stream (host-side events only; no device memory), 0 = off; setting it resets the totals. */
 int pp_set_option(pp_model* m, const char* key, int64_t value);
+
+/* Blocks until the stream is idle, then returns the summed duration (ms), matmul FLOPs and number of the GEMM
+ * launches (forward, input-gradient and weight-gradient GEMMs, split-K reduction included) bracketed since
+ * "time_gemm" was set or since the previous call, and resets the totals. */
+int pp_get_gemm_timing(pp_model* m, double* total_ms, double* total_flops, int64_t* launches);
 
 const char* pp_last_error(void);
 void pp_free(pp_model* m);

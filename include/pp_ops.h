@@ -26,13 +26,15 @@ int pp_op_gemm_nt(void* hip_stream, int dtype, const void* A_dev, int lda, const
 /* Causal softmax attention (Appendix "MHA with frozen heads", forward of every head; mask from the autoregressive
  * factorisation of Section 2.1).  qkv_dev: [B*S x 3*h*dh], columns q | k | v, head j at columns j*dh of each part
  * (q and k already rotated).  o_dev: [B*S x h*dh].  lse_dev: float [B*h*S], log-sum-exp of the scaled scores.
- * path as above. */
-int pp_op_attention_fwd(void* hip_stream, int dtype, const void* qkv_dev, void* o_dev, float* lse_dev, int B, int S, int h, int dh, int path);
+ * scratch_dev: 3 * B*h*dh*ceil(S/64)*64 bf16 elements, 16-byte aligned, used by the MFMA path (bf16, dh 64 or 128) for
+ * transposed operand copies; NULL selects the plain kernels.  path as above. */
+int pp_op_attention_fwd(void* hip_stream, int dtype, const void* qkv_dev, void* o_dev, float* lse_dev, void* scratch_dev,
+                        int B, int S, int h, int dh, int path);
 
 /* Backward of the above for all heads: dqkv_dev [B*S x 3*h*dh] receives dq | dk | dv (in the rotated frame);
  * D_dev: float [B*h*S] scratch (row sums of dO * O). */
 int pp_op_attention_bwd(void* hip_stream, int dtype, const void* qkv_dev, const void* o_dev, const float* lse_dev, const void* dO_dev,
-                        void* dqkv_dev, float* D_dev, int B, int S, int h, int dh, int path);
+                        void* dqkv_dev, float* D_dev, void* scratch_dev, int B, int S, int h, int dh, int path);
 
 #ifdef __cplusplus
 }

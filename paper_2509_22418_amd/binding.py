@@ -14,7 +14,7 @@ import numpy as np
 PP_F32, PP_BF16 = 0, 1
 PP_BYTES_PARAMS, PP_BYTES_STATE, PP_BYTES_WORKSPACE, PP_BYTES_SHADOW, PP_BYTES_ACTIVATIONS = range(5)
 EXPORTS = ["pp_query_bytes", "pp_init_model", "pp_set_tensor", "pp_get_tensor", "pp_set_trainable_mask", "pp_local_step",
-           "pp_outer_delta", "pp_synth_delta_sum", "pp_get_counters", "pp_set_option", "pp_last_error", "pp_free",
+           "pp_outer_delta", "pp_synth_delta_sum", "pp_get_counters", "pp_get_gemm_timing", "pp_set_option", "pp_last_error", "pp_free",
            "pp_op_gemm_nt", "pp_op_attention_fwd", "pp_op_attention_bwd"]
 
 
@@ -76,6 +76,8 @@ def load_library():
     lib.pp_synth_delta_sum.argtypes = [vp, vp, sz, C.POINTER(C.c_uint64), i32, C.c_float]
     lib.pp_get_counters.restype = C.c_int
     lib.pp_get_counters.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(i64)]
+    lib.pp_get_gemm_timing.restype = C.c_int
+    lib.pp_get_gemm_timing.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(i64)]
     lib.pp_set_option.restype = C.c_int
     lib.pp_set_option.argtypes = [vp, C.c_char_p, i64]
     lib.pp_last_error.restype = C.c_char_p
@@ -85,9 +87,9 @@ def load_library():
     lib.pp_op_gemm_nt.restype = C.c_int
     lib.pp_op_gemm_nt.argtypes = [vp, C.c_int, vp, C.c_int, vp, C.c_int, vp, C.c_int, C.c_int, C.c_int, C.c_int, vp, C.c_int, C.c_int, vp, C.c_int]
     lib.pp_op_attention_fwd.restype = C.c_int
-    lib.pp_op_attention_fwd.argtypes = [vp, C.c_int, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]
+    lib.pp_op_attention_fwd.argtypes = [vp, C.c_int, vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]
     lib.pp_op_attention_bwd.restype = C.c_int
-    lib.pp_op_attention_bwd.argtypes = [vp, C.c_int, vp, vp, vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]
+    lib.pp_op_attention_bwd.argtypes = [vp, C.c_int, vp, vp, vp, vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]
     _lib = lib
     return lib
 
@@ -154,6 +156,12 @@ def pp_get_counters(h):
     return dict(flops_fwd=f.value, flops_bwd=b.value, adamw_bytes=a.value, n_trainable=n.value)
 
 
+def pp_get_gemm_timing(h):
+    ms, fl, n = C.c_double(), C.c_double(), C.c_int64()
+    _check(load_library().pp_get_gemm_timing(h, C.byref(ms), C.byref(fl), C.byref(n)), "pp_get_gemm_timing")
+    return dict(ms=ms.value, flops=fl.value, launches=n.value)
+
+
 def pp_set_option(h, key: str, value: int):
     _check(load_library().pp_set_option(h, key.encode(), value), "pp_set_option")
 
@@ -168,12 +176,12 @@ def pp_op_gemm_nt(stream: int, dtype: int, A_ptr, lda, B_ptr, ldb, C_ptr, ldc, M
                                         scratch_ptr, path), "pp_op_gemm_nt")
 
 
-def pp_op_attention_fwd(stream: int, dtype: int, qkv_ptr, o_ptr, lse_ptr, B, S, h, dh, path=0):
-    _check(load_library().pp_op_attention_fwd(stream, dtype, qkv_ptr, o_ptr, lse_ptr, B, S, h, dh, path), "pp_op_attention_fwd")
+def pp_op_attention_fwd(stream: int, dtype: int, qkv_ptr, o_ptr, lse_ptr, scratch_ptr, B, S, h, dh, path=0):
+    _check(load_library().pp_op_attention_fwd(stream, dtype, qkv_ptr, o_ptr, lse_ptr, scratch_ptr, B, S, h, dh, path), "pp_op_attention_fwd")
 
 
-def pp_op_attention_bwd(stream: int, dtype: int, qkv_ptr, o_ptr, lse_ptr, dO_ptr, dqkv_ptr, D_ptr, B, S, h, dh, path=0):
-    _check(load_library().pp_op_attention_bwd(stream, dtype, qkv_ptr, o_ptr, lse_ptr, dO_ptr, dqkv_ptr, D_ptr, B, S, h, dh, path),
+def pp_op_attention_bwd(stream: int, dtype: int, qkv_ptr, o_ptr, lse_ptr, dO_ptr, dqkv_ptr, D_ptr, scratch_ptr, B, S, h, dh, path=0):
+    _check(load_library().pp_op_attention_bwd(stream, dtype, qkv_ptr, o_ptr, lse_ptr, dO_ptr, dqkv_ptr, D_ptr, scratch_ptr, B, S, h, dh, path),
            "pp_op_attention_bwd")
 
 
@@ -284,6 +292,9 @@ class LocalStepModel:
 
     def set_option(self, key: str, value: int):
         pp_set_option(self.h, key, value)
+
+    def gemm_timing(self):
+        return pp_get_gemm_timing(self.h)
 
     def memory_report(self) -> dict:
         return dict(params=self.bytes_params, state=self.bytes_state, workspace=self.bytes_ws, shadow=self.bytes_shadow,

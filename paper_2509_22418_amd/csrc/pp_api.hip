@@ -80,7 +80,7 @@ struct WsPlan {          // byte offsets into the workspace
   size_t act0, act_stride;          // per layer
   size_t a_x, a_n1, a_qkv, a_o, a_xm, a_n2, a_gu, a_a, a_rstd1, a_rstd2, a_lse;      // within a layer's block
   size_t xL, nf, rstdf, logits, rowloss, nvalid, dgpart;
-  size_t dx, dn, dA, dgu, dob, dqkv, Dattn;
+  size_t dx, dn, dA, dgu, dob, dqkv, Dattn, at;
   size_t fixed_end;      // everything above is mask independent
   size_t tA, tB, partial, partial_bytes, total;
   size_t act_bytes, shadow_bytes;
@@ -116,6 +116,7 @@ static WsPlan plan_ws(const pp_config& c, const Mask* mk) {
   p.rowloss = take(T * 4); p.nvalid = take(256); p.dgpart = take(64 * d * 4);
   p.dx = take(T * d * es); p.dn = take(T * d * es); p.dA = take(T * F * es); p.dgu = take(T * 2 * F * es);
   p.dob = take(T * d * es); p.dqkv = take(T * 3 * d * es); p.Dattn = take((size_t)c.max_batch * h * c.max_seq * 4);
+  p.at = take(c.dtype == PP_BF16 ? 3 * attn_scratch_elems(c.max_batch, c.max_seq, (int)h, (int)dh) * es : 0);
   p.fixed_end = off;
   // mask-dependent scratch for the weight-gradient GEMMs (operands transposed to K-contiguous form)
   Mask all{}; all.emb = all.norms = all.wo = all.lm = all.heads = all.ffn = true; all.fl = 0; all.fh = c.d_ff; all.hl = 0; all.hh = c.n_heads;
@@ -154,7 +155,31 @@ struct pp_model {
   int force_plain = 0;
   double flops_fwd = 0, flops_bwd = 0, adamw_bytes = 0;
   double* flop_acc = nullptr;
+  // optional GEMM timing: one event pair per GEMM launch, summed by pp_get_gemm_timing
+  int time_gemm = 0;
+  std::vector<hipEvent_t> ev;
+  size_t ev_used = 0;
+  double timed_flops = 0;
+  ~pp_model() { for (hipEvent_t e : ev) hipEventDestroy(e); }
 };
+
+namespace {
+struct GemmTimer {          // brackets the launches issued during its lifetime
+  pp_model* m; double flops; bool on = false; size_t idx = 0;
+  GemmTimer(pp_model* m_, double flops_) : m(m_), flops(flops_) {
+    if (!m->time_gemm) return;
+    if (m->ev_used + 2 > m->ev.size()) {
+      hipEvent_t a, b;
+      if (hipEventCreate(&a) != hipSuccess) return;
+      if (hipEventCreate(&b) != hipSuccess) { hipEventDestroy(a); return; }
+      m->ev.push_back(a); m->ev.push_back(b);
+    }
+    idx = m->ev_used; m->ev_used += 2; on = true;
+    hipEventRecord(m->ev[idx], m->st);
+  }
+  ~GemmTimer() { if (on) { hipEventRecord(m->ev[idx + 1], m->st); m->timed_flops += flops; } }
+};
+}  // namespace
 
 // ------------------------------------------------------------------------------------------------ helpers
 static int check_cfg(const pp_config* c) {
@@ -295,6 +320,11 @@ extern "C" void pp_free(pp_model* m) { delete m; }
 extern "C" int pp_set_option(pp_model* m, const char* key, int64_t value) {
   if (!m || !key) return fail(PP_EINVAL, "pp_set_option: NULL");
   if (!strcmp(key, "force_plain")) { m->force_plain = value != 0; return PP_OK; }
+  if (!strcmp(key, "time_gemm")) {
+    if (hipStreamSynchronize(m->st) != hipSuccess) return fail(PP_EHIP, "pp_set_option: stream sync failed");
+    m->time_gemm = value != 0; m->ev_used = 0; m->timed_flops = 0;
+    return PP_OK;
+  }
   return fail(PP_EINVAL, std::string("pp_set_option: unknown key ") + key);
 }
 
@@ -420,6 +450,7 @@ extern "C" int pp_set_trainable_mask(pp_model* m, const pp_mask* mask, void* sta
 static void gemm_nt(pp_model* m, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
                     int epi = EPI_STORE, const void* R = nullptr) {
   if (m->flop_acc) *m->flop_acc += 2.0 * M * N * K;
+  GemmTimer timer(m, 2.0 * M * N * K);
   if (m->cfg.dtype == PP_BF16 && !m->force_plain &&
       k_gemm_nt_mfma(m->st, A, lda, B, ldb, C, ldc, M, N, K, epi, R, 0, 1, nullptr) == 0) return;
   k_gemm_nt_plain(m->st, m->cfg.dtype, A, lda, B, ldb, C, ldc, M, N, K, epi, R, 0);
@@ -429,6 +460,7 @@ static void gemm_nt(pp_model* m, const void* A, int lda, const void* B, int ldb,
 // a long K: the K range is split over `splits` workgroup columns and summed in fixed order.
 static void gemm_dw(pp_model* m, const void* At, const void* Bt, float* G, int M, int N, int K) {
   if (m->flop_acc) *m->flop_acc += 2.0 * M * N * K;
+  GemmTimer timer(m, 2.0 * M * N * K);
   const size_t out_bytes = (size_t)M * N * 4;
   const long tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
   int splits = 1;
@@ -448,13 +480,13 @@ static void gemm_dw(pp_model* m, const void* At, const void* Bt, float* G, int M
 static void attn_fwd(pp_model* m, const void* qkv, void* o, float* lse, int B, int S) {
   const int h = m->cfg.n_heads, dh = m->cfg.d_model / h;
   if (m->flop_acc) *m->flop_acc += 4.0 * ((double)B * S * (S + 1) / 2) * m->cfg.d_model;
-  if (m->cfg.dtype == PP_BF16 && !m->force_plain && k_attn_fwd_mfma(m->st, qkv, o, lse, B, S, h, dh) == 0) return;
+  if (m->cfg.dtype == PP_BF16 && !m->force_plain && k_attn_fwd_mfma(m->st, qkv, o, lse, m->wsp + m->ws.at, B, S, h, dh) == 0) return;
   k_attn_fwd_plain(m->st, m->cfg.dtype, qkv, o, lse, B, S, h, dh);
 }
 static void attn_bwd(pp_model* m, const void* qkv, const void* o, const float* lse, const void* dO, void* dqkv, float* Dbuf, int B, int S) {
   const int h = m->cfg.n_heads, dh = m->cfg.d_model / h;
   if (m->flop_acc) *m->flop_acc += 8.0 * ((double)B * S * (S + 1) / 2) * m->cfg.d_model;
-  if (m->cfg.dtype == PP_BF16 && !m->force_plain && k_attn_bwd_mfma(m->st, qkv, o, lse, dO, dqkv, Dbuf, B, S, h, dh) == 0) return;
+  if (m->cfg.dtype == PP_BF16 && !m->force_plain && k_attn_bwd_mfma(m->st, qkv, o, lse, dO, dqkv, Dbuf, m->wsp + m->ws.at, B, S, h, dh) == 0) return;
   k_attn_bwd_plain(m->st, m->cfg.dtype, qkv, o, lse, dO, dqkv, Dbuf, B, S, h, dh);
 }
 
@@ -637,6 +669,22 @@ extern "C" int pp_synth_delta_sum(pp_model* m, float* dst_dev, size_t n, const u
   return PP_OK;
 }
 
+extern "C" int pp_get_gemm_timing(pp_model* m, double* total_ms, double* total_flops, int64_t* launches) {
+  if (!m) return fail(PP_EINVAL, "pp_get_gemm_timing: NULL model");
+  HIPCHECK(hipStreamSynchronize(m->st));
+  double ms = 0;
+  for (size_t i = 0; i + 1 < m->ev_used; i += 2) {
+    float t = 0.f;
+    HIPCHECK(hipEventElapsedTime(&t, m->ev[i], m->ev[i + 1]));
+    ms += t;
+  }
+  if (total_ms) *total_ms = ms;
+  if (total_flops) *total_flops = m->timed_flops;
+  if (launches) *launches = (int64_t)(m->ev_used / 2);
+  m->ev_used = 0; m->timed_flops = 0;
+  return PP_OK;
+}
+
 extern "C" int pp_get_counters(pp_model* m, double* flops_fwd, double* flops_bwd, double* adamw_bytes, int64_t* n_trainable) {
   if (!m) return fail(PP_EINVAL, "pp_get_counters: NULL model");
   if (flops_fwd) *flops_fwd = m->flops_fwd;
@@ -678,21 +726,21 @@ static int check_attn(int dtype, int B, int S, int h, int dh) {
   if (B < 1 || S < 1 || h < 1 || dh < 2 || dh % 2 || dh > 256 || S > 8192) return fail(PP_EINVAL, "attention: bad shape");
   return PP_OK;
 }
-extern "C" int pp_op_attention_fwd(void* hip_stream, int dtype, const void* qkv, void* o, float* lse, int B, int S, int h, int dh, int path) {
+extern "C" int pp_op_attention_fwd(void* hip_stream, int dtype, const void* qkv, void* o, float* lse, void* scratch, int B, int S, int h, int dh, int path) {
   if (!qkv || !o || !lse) return fail(PP_EINVAL, "pp_op_attention_fwd: NULL pointer");
   if (int rc = check_attn(dtype, B, S, h, dh)) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
-  if (!(path == 0 && dtype == PP_BF16 && k_attn_fwd_mfma(st, qkv, o, lse, B, S, h, dh) == 0)) k_attn_fwd_plain(st, dtype, qkv, o, lse, B, S, h, dh);
+  if (!(path == 0 && dtype == PP_BF16 && scratch && k_attn_fwd_mfma(st, qkv, o, lse, scratch, B, S, h, dh) == 0)) k_attn_fwd_plain(st, dtype, qkv, o, lse, B, S, h, dh);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(PP_EHIP, std::string("pp_op_attention_fwd: ") + hipGetErrorString(e));
   return PP_OK;
 }
 extern "C" int pp_op_attention_bwd(void* hip_stream, int dtype, const void* qkv, const void* o, const float* lse, const void* dO,
-                                   void* dqkv, float* Dbuf, int B, int S, int h, int dh, int path) {
+                                   void* dqkv, float* Dbuf, void* scratch, int B, int S, int h, int dh, int path) {
   if (!qkv || !o || !lse || !dO || !dqkv || !Dbuf) return fail(PP_EINVAL, "pp_op_attention_bwd: NULL pointer");
   if (int rc = check_attn(dtype, B, S, h, dh)) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
-  if (!(path == 0 && dtype == PP_BF16 && k_attn_bwd_mfma(st, qkv, o, lse, dO, dqkv, Dbuf, B, S, h, dh) == 0))
+  if (!(path == 0 && dtype == PP_BF16 && scratch && k_attn_bwd_mfma(st, qkv, o, lse, dO, dqkv, Dbuf, scratch, B, S, h, dh) == 0))
     k_attn_bwd_plain(st, dtype, qkv, o, lse, dO, dqkv, Dbuf, B, S, h, dh);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(PP_EHIP, std::string("pp_op_attention_bwd: ") + hipGetErrorString(e));

@@ -1,6 +1,504 @@
-// bf16 MFMA causal attention for gfx950 -- placeholder until the tiled kernels land: reports "unsupported".
+// bf16 MFMA causal attention for gfx950 (head dim 64 or 128): forward with online softmax, and a backward made of
+// two kernels (dQ; dK and dV) so that every output element is produced by exactly one workgroup in a fixed order
+// (run-to-run reproducible, no float atomics).
+//
+// Orientation.  All score-shaped products are formed TRANSPOSED with respect to the quantity whose softmax
+// statistics they need, so that one lane owns one softmax row:
+//   forward / dQ kernel:  S^T[key][query] = K Q^T   -> lane column = query, 16 keys per lane and 32x32 tile
+//   dK,dV kernel:         S[query][key]   = Q K^T   -> lane column = key (its dK/dV row), 16 queries per lane
+// The 32x32 MFMA accumulator gives lane (l) the rows 8*(r/4) + 4*(l/32) + r%4 of column l%32.  Eight consecutive
+// accumulator registers therefore hold, for lane half h, the rows {4h..4h+3, 8+4h..8+4h+3} of a 16-row group: exactly
+// a valid K-operand of the next MFMA if the OTHER operand enumerates the contraction index in the same order.
+// That other operand always comes from a tensor stored "attention-transposed":
+//   AT(X)[(b*h + head)*dh + c][perm(s)] = X[b, s, head, c],   perm(s) = s with bits 2 and 3 swapped,
+// rows padded with zeros to a multiple of 64 positions.  With that layout one 16-byte LDS read yields the operand,
+// and P / dS never leave registers.
 #include "pp_kernels.h"
+#include "pp_dev.h"
+
 namespace pp {
-int k_attn_fwd_mfma(hipStream_t, const void*, void*, float*, int, int, int, int) { return 1; }
-int k_attn_bwd_mfma(hipStream_t, const void*, const void*, const float*, const void*, void*, float*, int, int, int, int) { return 1; }
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+#define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) { return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16); }
+__device__ __forceinline__ bf16x8 pack8(const f32x16& v, int base) {
+  u32x4 w;
+  w[0] = pack_bf16x2(v[base + 0], v[base + 1]);
+  w[1] = pack_bf16x2(v[base + 2], v[base + 3]);
+  w[2] = pack_bf16x2(v[base + 4], v[base + 5]);
+  w[3] = pack_bf16x2(v[base + 6], v[base + 7]);
+  return __builtin_bit_cast(bf16x8, w);
 }
+__device__ __forceinline__ void zero16(f32x16& v) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r) v[r] = 0.f;
+}
+
+// ------------------------------------------------------------------------------------------ AT-layout transposes
+// src: rows = positions (ld_src elements apart), head `head` at columns col0 + head*dh; dst: AT layout, row length Sp.
+__global__ void head_transpose_kernel(const bf16_t* __restrict__ src, int ld_src, int col0, bf16_t* __restrict__ dst,
+                                      int S, int Sp, int h, int dh) {
+  __shared__ uint16_t tile[64][66];
+  const int s0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+  const int bh = blockIdx.z, b = bh / h, head = bh % h;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const bf16_t* sp = src + (size_t)b * S * ld_src + col0 + (size_t)head * dh;
+  for (int i = ty; i < 64; i += 4) {
+    const int s = s0 + i;
+    tile[i][tx] = (s < S) ? sp[(size_t)s * ld_src + c0 + tx].bits : (uint16_t)0;
+  }
+  __syncthreads();
+  const int sperm = (tx & ~12) | ((tx & 4) << 1) | ((tx & 8) >> 1);          // destination slot tx holds source position sperm
+  uint16_t* dp = reinterpret_cast<uint16_t*>(dst) + ((size_t)bh * dh + c0) * Sp + s0;
+  for (int i = ty; i < 64; i += 4) dp[(size_t)i * Sp + tx] = tile[sperm][i];
+}
+static void head_transpose(hipStream_t st, const void* src, int ld_src, int col0, void* dst, int B, int S, int h, int dh) {
+  const int Sp = (S + 63) / 64 * 64;
+  dim3 grid(Sp / 64, dh / 64, B * h);
+  head_transpose_kernel<<<grid, 256, 0, st>>>((const bf16_t*)src, ld_src, col0, (bf16_t*)dst, S, Sp, h, dh);
+}
+
+// ------------------------------------------------------------------------------------------ tile staging helpers
+// A tile is ROWS x (CPR 16-byte chunks); chunk c of row r lives at r*CPR + (c ^ (r & 7)).  256 threads.
+template <int ROWS, int CPR>
+struct Stage {
+  static constexpr int N = ROWS * CPR / 256;
+  template <class F>
+  static __device__ __forceinline__ void load(u32x4 (&reg)[N], F&& src_of) {          // src_of(row, chunk) -> const bf16_t*
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const int q = threadIdx.x + 256 * i;
+      reg[i] = *reinterpret_cast<const u32x4*>(src_of(q / CPR, q % CPR));
+    }
+  }
+  static __device__ __forceinline__ void store(const u32x4 (&reg)[N], u32x4* tile) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const int q = threadIdx.x + 256 * i;
+      const int row = q / CPR, c = q % CPR;
+      tile[row * CPR + (c ^ (row & 7))] = reg[i];
+    }
+  }
+};
+template <int CPR>
+__device__ __forceinline__ bf16x8 frag(const u32x4* tile, int row, int chunk) {
+  return __builtin_bit_cast(bf16x8, tile[row * CPR + (chunk ^ (row & 7))]);
+}
+
+constexpr float LOG2E = 1.4426950408889634f, LN2 = 0.6931471805599453f;
+
+// ------------------------------------------------------------------------------------------ forward
+// grid (ceil(S/128), h, B), 256 threads: wave w owns queries q0 + 32w .. +31; KV tiles of 64 keys.
+template <int DH>
+__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ vt,
+                                                           bf16_t* __restrict__ o, float* __restrict__ lse, int S, int Sp, int h) {
+  constexpr int KS = DH / 16, CT = DH / 32, CPRK = DH / 8;
+  extern __shared__ u32x4 lds[];
+  constexpr int K_CH = 64 * CPRK, V_CH = DH * 8, ST_CH = K_CH + V_CH;
+  const int d = h * DH, ld = 3 * d;
+  const int qblk = gridDim.x - 1 - blockIdx.x;          // heaviest (latest) query blocks first
+  const int head = blockIdx.y, b = blockIdx.z;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lh = lane >> 5;
+  const int q0 = qblk * 128, qw0 = q0 + wave * 32;
+  const int q = qw0 + l32;
+  const bf16_t* base = qkv + (size_t)b * S * ld + (size_t)head * DH;
+  const bf16_t* vtb = vt + ((size_t)(b * h + head) * DH) * Sp;
+  const int n_tiles = min((q0 + 128 + 63) / 64, (S + 63) / 64);
+
+  bf16x8 qf[KS];
+  {
+    const bf16_t* qp = base + (size_t)min(q, S - 1) * ld + 8 * lh;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) qf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qp + 16 * s));
+  }
+  f32x16 oacc[CT];
+#pragma unroll
+  for (int c = 0; c < CT; ++c) zero16(oacc[c]);
+  float m_run = -INFINITY, l_run = 0.f;
+  const float sc2 = LOG2E / sqrtf((float)DH);
+
+  u32x4 rk[Stage<64, CPRK>::N], rv[Stage<DH, 8>::N];
+  auto ksrc = [&](int kv0) { return [=](int row, int c) { return base + (size_t)min(kv0 + row, S - 1) * ld + d + c * 8; }; };
+  auto vsrc = [&](int kv0) { return [=](int row, int c) { return vtb + (size_t)row * Sp + kv0 + c * 8; }; };
+  Stage<64, CPRK>::load(rk, ksrc(0));
+  Stage<DH, 8>::load(rv, vsrc(0));
+  Stage<64, CPRK>::store(rk, lds);
+  Stage<DH, 8>::store(rv, lds + K_CH);
+  __syncthreads();
+
+  for (int j = 0; j < n_tiles; ++j) {
+    const u32x4* kt = lds + (j & 1) * ST_CH;
+    const u32x4* vtile = kt + K_CH;
+    u32x4* nxt = lds + ((j + 1) & 1) * ST_CH;
+    const int kv0 = j * 64, kvn = min(j + 1, n_tiles - 1) * 64;
+    Stage<64, CPRK>::load(rk, ksrc(kvn));
+    Stage<DH, 8>::load(rv, vsrc(kvn));
+    __builtin_amdgcn_sched_barrier(0);
+    if (kv0 <= qw0 + 31) {          // wave-uniform: some key of the tile is visible to some query of this wave
+      f32x16 sacc[2];
+      zero16(sacc[0]); zero16(sacc[1]);
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) sacc[mt] = MFMA(frag<CPRK>(kt, mt * 32 + l32, 2 * s + lh), qf[s], sacc[mt]);
+      }
+      float tmax = -INFINITY;
+      const bool diag = kv0 + 63 > qw0;          // some (key, query) pair of the tile may be masked
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float v = sacc[mt][r] * sc2;
+          if (diag) { const int key = kv0 + mt * 32 + 8 * (r >> 2) + 4 * lh + (r & 3); if (key > q) v = -INFINITY; }
+          sacc[mt][r] = v;
+          tmax = fmaxf(tmax, v);
+        }
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+      const float m_new = fmaxf(m_run, tmax);
+      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;          // whole row masked so far (only for padded queries)
+      const float alpha = exp2f(m_run - m_use);
+      float psum = 0.f;
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { const float p = exp2f(sacc[mt][r] - m_use); sacc[mt][r] = p; psum += p; }
+      l_run = l_run * alpha + psum;
+      m_run = m_new;
+#pragma unroll
+      for (int c = 0; c < CT; ++c)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[c][r] *= alpha;
+      bf16x8 pf[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) pf[t] = pack8(sacc[t >> 1], 8 * (t & 1));
+#pragma unroll
+      for (int c = 0; c < CT; ++c)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) oacc[c] = MFMA(frag<8>(vtile, c * 32 + l32, 2 * t + lh), pf[t], oacc[c]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    Stage<64, CPRK>::store(rk, nxt);
+    Stage<DH, 8>::store(rv, nxt + K_CH);
+    __syncthreads();
+  }
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  if (q < S) {
+    const float inv = 1.0f / l_tot;
+    bf16_t* op = o + ((size_t)b * S + q) * d + (size_t)head * DH + 4 * lh;
+#pragma unroll
+    for (int c = 0; c < CT; ++c)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        u32x2 w;
+        w[0] = pack_bf16x2(oacc[c][4 * g] * inv, oacc[c][4 * g + 1] * inv);
+        w[1] = pack_bf16x2(oacc[c][4 * g + 2] * inv, oacc[c][4 * g + 3] * inv);
+        *reinterpret_cast<u32x2*>(op + c * 32 + 8 * g) = w;
+      }
+    if (lh == 0) lse[((size_t)b * h + head) * S + q] = (m_run + log2f(l_tot)) * LN2;
+  }
+}
+
+// ------------------------------------------------------------------------------------------ backward: dQ
+// Same blocking as the forward.  Per KV tile: S^T = K Q^T, dP^T = V dO^T, dS^T = P^T * (dP^T - D), dQ^T += AT(K) dS^T.
+template <int DH>
+__global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ kt_at,
+                                                              const bf16_t* __restrict__ dO, const float* __restrict__ lse,
+                                                              const float* __restrict__ Dbuf, bf16_t* __restrict__ dqkv, int S, int Sp, int h) {
+  constexpr int KS = DH / 16, CT = DH / 32, CPRK = DH / 8;
+  extern __shared__ u32x4 lds[];
+  constexpr int K_CH = 64 * CPRK, T_CH = DH * 8, ST_CH = 2 * K_CH + T_CH;
+  const int d = h * DH, ld = 3 * d;
+  const int qblk = gridDim.x - 1 - blockIdx.x;
+  const int head = blockIdx.y, b = blockIdx.z;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lh = lane >> 5;
+  const int q0 = qblk * 128, qw0 = q0 + wave * 32;
+  const int q = qw0 + l32, qc = min(q, S - 1);
+  const bf16_t* base = qkv + (size_t)b * S * ld + (size_t)head * DH;
+  const bf16_t* ktb = kt_at + ((size_t)(b * h + head) * DH) * Sp;
+  const int n_tiles = min((q0 + 128 + 63) / 64, (S + 63) / 64);
+  const float scale = 1.0f / sqrtf((float)DH), sc2 = LOG2E * scale;
+
+  bf16x8 qf[KS], dof[KS];
+  {
+    const bf16_t* qp = base + (size_t)qc * ld + 8 * lh;
+    const bf16_t* dp = dO + ((size_t)b * S + qc) * d + (size_t)head * DH + 8 * lh;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      qf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qp + 16 * s));
+      dof[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(dp + 16 * s));
+    }
+  }
+  const size_t stat = ((size_t)b * h + head) * S + qc;
+  const float lse2 = lse[stat] * LOG2E, Dq = Dbuf[stat];
+  f32x16 dqacc[CT];
+#pragma unroll
+  for (int c = 0; c < CT; ++c) zero16(dqacc[c]);
+
+  u32x4 rk[Stage<64, CPRK>::N], rv[Stage<64, CPRK>::N], rt[Stage<DH, 8>::N];
+  auto ksrc = [&](int kv0) { return [=](int row, int c) { return base + (size_t)min(kv0 + row, S - 1) * ld + d + c * 8; }; };
+  auto vsrc = [&](int kv0) { return [=](int row, int c) { return base + (size_t)min(kv0 + row, S - 1) * ld + 2 * d + c * 8; }; };
+  auto tsrc = [&](int kv0) { return [=](int row, int c) { return ktb + (size_t)row * Sp + kv0 + c * 8; }; };
+  Stage<64, CPRK>::load(rk, ksrc(0));
+  Stage<64, CPRK>::load(rv, vsrc(0));
+  Stage<DH, 8>::load(rt, tsrc(0));
+  Stage<64, CPRK>::store(rk, lds);
+  Stage<64, CPRK>::store(rv, lds + K_CH);
+  Stage<DH, 8>::store(rt, lds + 2 * K_CH);
+  __syncthreads();
+
+  for (int j = 0; j < n_tiles; ++j) {
+    const u32x4* ktile = lds + (j & 1) * ST_CH;
+    const u32x4* vtile = ktile + K_CH;
+    const u32x4* ttile = ktile + 2 * K_CH;
+    u32x4* nxt = lds + ((j + 1) & 1) * ST_CH;
+    const int kv0 = j * 64, kvn = min(j + 1, n_tiles - 1) * 64;
+    Stage<64, CPRK>::load(rk, ksrc(kvn));
+    Stage<64, CPRK>::load(rv, vsrc(kvn));
+    Stage<DH, 8>::load(rt, tsrc(kvn));
+    __builtin_amdgcn_sched_barrier(0);
+    if (kv0 <= qw0 + 31) {
+      f32x16 sacc[2], dpacc[2];
+      zero16(sacc[0]); zero16(sacc[1]); zero16(dpacc[0]); zero16(dpacc[1]);
+#pragma unroll
+      for (int s = 0; s < KS; ++s)
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+          sacc[mt] = MFMA(frag<CPRK>(ktile, mt * 32 + l32, 2 * s + lh), qf[s], sacc[mt]);
+          dpacc[mt] = MFMA(frag<CPRK>(vtile, mt * 32 + l32, 2 * s + lh), dof[s], dpacc[mt]);
+        }
+      const bool diag = kv0 + 63 > qw0;
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float p = exp2f(sacc[mt][r] * sc2 - lse2);
+          if (diag) { const int key = kv0 + mt * 32 + 8 * (r >> 2) + 4 * lh + (r & 3); if (key > q) p = 0.f; }
+          sacc[mt][r] = p * (dpacc[mt][r] - Dq);
+        }
+      bf16x8 dsf[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) dsf[t] = pack8(sacc[t >> 1], 8 * (t & 1));
+#pragma unroll
+      for (int c = 0; c < CT; ++c)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) dqacc[c] = MFMA(frag<8>(ttile, c * 32 + l32, 2 * t + lh), dsf[t], dqacc[c]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    Stage<64, CPRK>::store(rk, nxt);
+    Stage<64, CPRK>::store(rv, nxt + K_CH);
+    Stage<DH, 8>::store(rt, nxt + 2 * K_CH);
+    __syncthreads();
+  }
+  if (q < S) {
+    bf16_t* op = dqkv + ((size_t)b * S + q) * ld + (size_t)head * DH + 4 * lh;
+#pragma unroll
+    for (int c = 0; c < CT; ++c)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        u32x2 w;
+        w[0] = pack_bf16x2(dqacc[c][4 * g] * scale, dqacc[c][4 * g + 1] * scale);
+        w[1] = pack_bf16x2(dqacc[c][4 * g + 2] * scale, dqacc[c][4 * g + 3] * scale);
+        *reinterpret_cast<u32x2*>(op + c * 32 + 8 * g) = w;
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------------ backward: dK, dV
+// grid (ceil(S/128), h, B): wave w owns keys k0 + 32w .. +31 (lane column = key); query tiles of 64 from the diagonal on.
+// Per query tile: S = Q K^T, dP = dO V^T, P = exp(S - lse), dS = P * (dP - D); dV^T += AT(dO) P, dK^T += AT(Q) dS.
+template <int DH>
+__global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ qt_at,
+                                                               const bf16_t* __restrict__ dO, const bf16_t* __restrict__ dot_at,
+                                                               const float* __restrict__ lse, const float* __restrict__ Dbuf,
+                                                               bf16_t* __restrict__ dqkv, int S, int Sp, int h) {
+  constexpr int KS = DH / 16, CT = DH / 32, CPRK = DH / 8;
+  extern __shared__ u32x4 lds[];
+  constexpr int Q_CH = 64 * CPRK, T_CH = DH * 8, ST_CH = 2 * Q_CH + 2 * T_CH + 32;          // + 64 lse and 64 D floats (32 chunks)
+  const int d = h * DH, ld = 3 * d;
+  const int kblk = blockIdx.x;          // earliest key blocks see the most queries: already first
+  const int head = blockIdx.y, b = blockIdx.z;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lh = lane >> 5;
+  const int k0 = kblk * 128, kw0 = k0 + wave * 32;
+  const int key = kw0 + l32, keyc = min(key, S - 1);
+  const bf16_t* base = qkv + (size_t)b * S * ld + (size_t)head * DH;
+  const bf16_t* qtb = qt_at + ((size_t)(b * h + head) * DH) * Sp;
+  const bf16_t* dotb = dot_at + ((size_t)(b * h + head) * DH) * Sp;
+  const bf16_t* dob = dO + (size_t)b * S * d + (size_t)head * DH;
+  const float* lseb = lse + ((size_t)b * h + head) * S;
+  const float* Db = Dbuf + ((size_t)b * h + head) * S;
+  const int t_first = k0 / 64, t_end = (S + 63) / 64;
+  const float scale = 1.0f / sqrtf((float)DH), sc2 = LOG2E * scale;
+
+  bf16x8 kf[KS], vf[KS];
+  {
+    const bf16_t* kp = base + (size_t)keyc * ld + d + 8 * lh;
+    const bf16_t* vp = base + (size_t)keyc * ld + 2 * d + 8 * lh;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      kf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(kp + 16 * s));
+      vf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(vp + 16 * s));
+    }
+  }
+  f32x16 dkacc[CT], dvacc[CT];
+#pragma unroll
+  for (int c = 0; c < CT; ++c) { zero16(dkacc[c]); zero16(dvacc[c]); }
+
+  u32x4 rq[Stage<64, CPRK>::N], rdo[Stage<64, CPRK>::N], rqt[Stage<DH, 8>::N], rdot[Stage<DH, 8>::N];
+  float rstat = 0.f;          // threads 0..63: lse of query row tid; 64..127: D of query row tid-64
+  auto qsrc = [&](int qq0) { return [=](int row, int c) { return base + (size_t)min(qq0 + row, S - 1) * ld + c * 8; }; };
+  auto dosrc = [&](int qq0) { return [=](int row, int c) { return dob + (size_t)min(qq0 + row, S - 1) * d + c * 8; }; };
+  auto qtsrc = [&](int qq0) { return [=](int row, int c) { return qtb + (size_t)row * Sp + qq0 + c * 8; }; };
+  auto dotsrc = [&](int qq0) { return [=](int row, int c) { return dotb + (size_t)row * Sp + qq0 + c * 8; }; };
+  auto load_stat = [&](int qq0) {
+    if (threadIdx.x < 64) rstat = lseb[min(qq0 + (int)threadIdx.x, S - 1)] * LOG2E;
+    else if (threadIdx.x < 128) rstat = Db[min(qq0 + (int)threadIdx.x - 64, S - 1)];
+  };
+  auto store_all = [&](u32x4* stage) {
+    Stage<64, CPRK>::store(rq, stage);
+    Stage<64, CPRK>::store(rdo, stage + Q_CH);
+    Stage<DH, 8>::store(rqt, stage + 2 * Q_CH);
+    Stage<DH, 8>::store(rdot, stage + 2 * Q_CH + T_CH);
+    if (threadIdx.x < 128) reinterpret_cast<float*>(stage + 2 * Q_CH + 2 * T_CH)[threadIdx.x] = rstat;
+  };
+  Stage<64, CPRK>::load(rq, qsrc(t_first * 64));
+  Stage<64, CPRK>::load(rdo, dosrc(t_first * 64));
+  Stage<DH, 8>::load(rqt, qtsrc(t_first * 64));
+  Stage<DH, 8>::load(rdot, dotsrc(t_first * 64));
+  load_stat(t_first * 64);
+  store_all(lds);
+  __syncthreads();
+
+  for (int t = t_first; t < t_end; ++t) {
+    const int it = t - t_first;
+    const u32x4* qtile = lds + (it & 1) * ST_CH;
+    const u32x4* dotile = qtile + Q_CH;
+    const u32x4* qttile = qtile + 2 * Q_CH;
+    const u32x4* dottile = qttile + T_CH;
+    const float* stat = reinterpret_cast<const float*>(qtile + 2 * Q_CH + 2 * T_CH);
+    u32x4* nxt = lds + ((it + 1) & 1) * ST_CH;
+    const int qq0 = t * 64, qqn = min(t + 1, t_end - 1) * 64;
+    Stage<64, CPRK>::load(rq, qsrc(qqn));
+    Stage<64, CPRK>::load(rdo, dosrc(qqn));
+    Stage<DH, 8>::load(rqt, qtsrc(qqn));
+    Stage<DH, 8>::load(rdot, dotsrc(qqn));
+    load_stat(qqn);
+    __builtin_amdgcn_sched_barrier(0);
+    if (qq0 + 63 >= kw0) {          // wave-uniform: some query of the tile sees some key of this wave
+      f32x16 sacc[2], dpacc[2];
+      zero16(sacc[0]); zero16(sacc[1]); zero16(dpacc[0]); zero16(dpacc[1]);
+#pragma unroll
+      for (int s = 0; s < KS; ++s)
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+          sacc[mt] = MFMA(frag<CPRK>(qtile, mt * 32 + l32, 2 * s + lh), kf[s], sacc[mt]);
+          dpacc[mt] = MFMA(frag<CPRK>(dotile, mt * 32 + l32, 2 * s + lh), vf[s], dpacc[mt]);
+        }
+      const bool edge = (qq0 < kw0 + 31) || (qq0 + 63 >= S);          // causal boundary or padded queries inside the tile
+      f32x16 pacc[2];
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int rowb = mt * 32 + 8 * g + 4 * lh;          // 4 consecutive query rows of this lane
+          const float4 l4 = *reinterpret_cast<const float4*>(stat + rowb);
+          const float4 d4 = *reinterpret_cast<const float4*>(stat + 64 + rowb);
+          const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, ds[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int r = 4 * g + e;
+            float p = exp2f(sacc[mt][r] * sc2 - ls[e]);
+            if (edge) { const int qq = qq0 + rowb + e; if (key > qq || qq >= S) p = 0.f; }
+            pacc[mt][r] = p;
+            sacc[mt][r] = p * (dpacc[mt][r] - ds[e]);
+          }
+        }
+      bf16x8 pf[4], dsf[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { pf[u] = pack8(pacc[u >> 1], 8 * (u & 1)); dsf[u] = pack8(sacc[u >> 1], 8 * (u & 1)); }
+#pragma unroll
+      for (int c = 0; c < CT; ++c)
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          dvacc[c] = MFMA(frag<8>(dottile, c * 32 + l32, 2 * u + lh), pf[u], dvacc[c]);
+          dkacc[c] = MFMA(frag<8>(qttile, c * 32 + l32, 2 * u + lh), dsf[u], dkacc[c]);
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    store_all(nxt);
+    __syncthreads();
+  }
+  if (key < S) {
+    bf16_t* kp = dqkv + ((size_t)b * S + key) * ld + d + (size_t)head * DH + 4 * lh;
+    bf16_t* vp = kp + d;
+#pragma unroll
+    for (int c = 0; c < CT; ++c)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        u32x2 wk, wv;
+        wk[0] = pack_bf16x2(dkacc[c][4 * g] * scale, dkacc[c][4 * g + 1] * scale);
+        wk[1] = pack_bf16x2(dkacc[c][4 * g + 2] * scale, dkacc[c][4 * g + 3] * scale);
+        wv[0] = pack_bf16x2(dvacc[c][4 * g], dvacc[c][4 * g + 1]);
+        wv[1] = pack_bf16x2(dvacc[c][4 * g + 2], dvacc[c][4 * g + 3]);
+        *reinterpret_cast<u32x2*>(kp + c * 32 + 8 * g) = wk;
+        *reinterpret_cast<u32x2*>(vp + c * 32 + 8 * g) = wv;
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------------ host side
+template <class K>
+static bool set_lds(K kern, int bytes) {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, bytes) == hipSuccess;
+}
+
+size_t attn_scratch_elems(int B, int S, int h, int dh) { return (size_t)B * h * dh * ((S + 63) / 64 * 64); }
+
+template <int DH>
+static int fwd_launch(hipStream_t st, const void* qkv, void* o, float* lse, void* at0, int B, int S, int h) {
+  static bool ok = set_lds(attn_fwd_kernel<DH>, 2 * (64 * (DH / 8) + DH * 8) * 16);
+  if (!ok) return 1;
+  const int Sp = (S + 63) / 64 * 64, d = h * DH;
+  head_transpose(st, qkv, 3 * d, 2 * d, at0, B, S, h, DH);          // AT(V)
+  dim3 grid((S + 127) / 128, h, B);
+  attn_fwd_kernel<DH><<<grid, 256, 2 * (64 * (DH / 8) + DH * 8) * 16, st>>>((const bf16_t*)qkv, (const bf16_t*)at0, (bf16_t*)o, lse, S, Sp, h);
+  return 0;
+}
+template <int DH>
+static int bwd_launch(hipStream_t st, const void* qkv, const void* o, const float* lse, const void* dO, void* dqkv, float* Dbuf,
+                      void* at0, void* at1, void* at2, int B, int S, int h) {
+  constexpr int DQ_LDS = 2 * (2 * 64 * (DH / 8) + DH * 8) * 16;
+  constexpr int DKV_LDS = 2 * (2 * 64 * (DH / 8) + 2 * DH * 8 + 32) * 16;
+  static bool ok = set_lds(attn_bwd_dq_kernel<DH>, DQ_LDS) && set_lds(attn_bwd_dkv_kernel<DH>, DKV_LDS);
+  if (!ok) return 1;
+  const int Sp = (S + 63) / 64 * 64, d = h * DH;
+  k_attn_D(st, 1, o, dO, Dbuf, B, S, h, DH);
+  head_transpose(st, qkv, 3 * d, d, at0, B, S, h, DH);          // AT(K)
+  head_transpose(st, qkv, 3 * d, 0, at1, B, S, h, DH);          // AT(Q)
+  head_transpose(st, dO, d, 0, at2, B, S, h, DH);               // AT(dO)
+  dim3 grid((S + 127) / 128, h, B);
+  attn_bwd_dq_kernel<DH><<<grid, 256, DQ_LDS, st>>>((const bf16_t*)qkv, (const bf16_t*)at0, (const bf16_t*)dO, lse, Dbuf, (bf16_t*)dqkv, S, Sp, h);
+  attn_bwd_dkv_kernel<DH><<<grid, 256, DKV_LDS, st>>>((const bf16_t*)qkv, (const bf16_t*)at1, (const bf16_t*)dO, (const bf16_t*)at2, lse, Dbuf,
+                                                      (bf16_t*)dqkv, S, Sp, h);
+  return 0;
+}
+
+// scratch: 3 * attn_scratch_elems(B,S,h,dh) bf16 elements (AT-layout copies), 16-byte aligned
+int k_attn_fwd_mfma(hipStream_t st, const void* qkv, void* o, float* lse, void* scratch, int B, int S, int h, int dh) {
+  if (!scratch || (dh != 64 && dh != 128) || S < 1) return 1;
+  return dh == 64 ? fwd_launch<64>(st, qkv, o, lse, scratch, B, S, h) : fwd_launch<128>(st, qkv, o, lse, scratch, B, S, h);
+}
+int k_attn_bwd_mfma(hipStream_t st, const void* qkv, const void* o, const float* lse, const void* dO, void* dqkv, float* Dbuf,
+                    void* scratch, int B, int S, int h, int dh) {
+  if (!scratch || (dh != 64 && dh != 128) || S < 1) return 1;
+  const size_t n = attn_scratch_elems(B, S, h, dh);
+  bf16_t* s0 = (bf16_t*)scratch;
+  return dh == 64 ? bwd_launch<64>(st, qkv, o, lse, dO, dqkv, Dbuf, s0, s0 + n, s0 + 2 * n, B, S, h)
+                  : bwd_launch<128>(st, qkv, o, lse, dO, dqkv, Dbuf, s0, s0 + n, s0 + 2 * n, B, S, h);
+}
+
+}  // namespace pp

@@ -107,9 +107,10 @@ def test_attention_fwd_bwd_matches_definition(B, S, h, dh):
         lse_d = torch.zeros(B * h * S, dtype=torch.float32, device="cuda")
         D_d = torch.zeros(B * h * S, dtype=torch.float32, device="cuda")
         dqkv_d = torch.zeros((T, 3 * d), dtype=torch.int16, device="cuda")
-        pp.pp_op_attention_fwd(st, pp.PP_BF16, qkv_d.data_ptr(), o_d.data_ptr(), lse_d.data_ptr(), B, S, h, dh, path)
+        scratch = torch.zeros(3 * B * h * dh * ((S + 63) // 64 * 64), dtype=torch.int16, device="cuda")
+        pp.pp_op_attention_fwd(st, pp.PP_BF16, qkv_d.data_ptr(), o_d.data_ptr(), lse_d.data_ptr(), scratch.data_ptr(), B, S, h, dh, path)
         pp.pp_op_attention_bwd(st, pp.PP_BF16, qkv_d.data_ptr(), o_d.data_ptr(), lse_d.data_ptr(), dO_d.data_ptr(), dqkv_d.data_ptr(),
-                               D_d.data_ptr(), B, S, h, dh, path)
+                               D_d.data_ptr(), scratch.data_ptr(), B, S, h, dh, path)
         torch.cuda.synchronize()
         o = from_bf16(o_d)
         err = np.max(np.abs(o - o_ref.reshape(T, d)))

@@ -1,0 +1,67 @@
+"""Outer pseudo-gradient step (Alg. 1: delta, count normalisation, Nesterov OuterOpt) and the on-device synthetic
+deltas, HIP path vs oracle / host generator."""
+import numpy as np
+import pytest
+import torch
+
+import pp_inputs as gen
+import paper_2509_22418_amd as pp
+from oracle import pp_oracle as O
+from harness import HP, make_gpu_model, frozen_bytes_equal
+
+pytestmark = pytest.mark.gpu
+
+SMALL = dict(n_layers=2, d_model=256, n_heads=2, d_ff=512, vocab=512, batch=2, seq=64, dtype="bf16")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_outer_step_matches_oracle(dtype):
+    cfg = gen.make_config("tiny", **dict(SMALL, dtype=dtype))
+    weights = gen.make_weights(cfg, seed=21)
+    mask = gen.ffn_slice_mask(cfg, 2, 4)
+    m = make_gpu_model(cfg, weights, mask)
+    segs = O.mask_segments(cfg, mask)
+    theta_g0 = O.pack(O.to_f64(weights), segs)
+    n = theta_g0.size
+    for h in range(2):          # two local steps so that theta_l != theta_g
+        tok, tgt = gen.make_tokens(cfg, seed=21, step=h)
+        m.step(*m.upload_tokens(tok, tgt), HP)
+    names = gen.tensor_shapes(cfg)
+    theta_l = O.pack({k: m.get_weight(k, s).astype(np.float64) for k, s in names.items()}, segs)
+    assert np.any(theta_l != theta_g0)
+    keys = [gen.stream_key(77, gen.STREAM_DELTAS, j + 1) for j in range(31)]
+    others_ref = gen.synthetic_delta_sum(77, n, 31, 1e-4)
+    tg = torch.from_numpy(theta_g0.astype(np.float32)).cuda()
+    mom = torch.zeros(n, dtype=torch.float32, device="cuda")
+    others = torch.empty(n, dtype=torch.float32, device="cuda")
+    delta = torch.empty(n, dtype=torch.float32, device="cuda")
+    pp.pp_synth_delta_sum(m.h, others.data_ptr(), n, keys, 1e-4)
+    torch.cuda.synchronize()
+    got_others = others.cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(got_others - others_ref)) <= 1e-6 * np.max(np.abs(others_ref))          # fp32 rounding of an fp64 sum
+    buf = np.zeros(n)
+    cur = theta_g0.astype(np.float32).astype(np.float64)
+    for rnd, (lr, mu, cnt) in enumerate([(0.7, 0.9, 32.0), (0.4, 0.9, 1.0)]):
+        opt = pp.PPOuter(lr, mu, 1, cnt)
+        pp.pp_outer_delta(m.h, tg.data_ptr(), mom.data_ptr(), others.data_ptr(), opt, delta.data_ptr())
+        torch.cuda.synchronize()
+        ref_new, buf, ref_delta = O.outer_step(cur, theta_l, got_others, buf, lr, mu, cnt)
+        np.testing.assert_allclose(delta.cpu().numpy(), ref_delta, rtol=2e-5, atol=1e-9)
+        np.testing.assert_allclose(tg.cpu().numpy(), ref_new, rtol=2e-6, atol=1e-8)
+        np.testing.assert_allclose(mom.cpu().numpy(), buf, rtol=2e-5, atol=1e-9)
+        # the local copy restarts from the new global values: masters == theta_g, weights == storage rounding of it
+        assert np.array_equal(m.get_state("p"), tg.cpu().numpy())
+        now = O.pack({k: m.get_weight(k, s).astype(np.float64) for k, s in names.items()}, segs)
+        expect = tg.cpu().numpy()
+        expect = gen.round_to_bf16(expect) if dtype == "bf16" else expect
+        assert np.array_equal(now.astype(np.float32), expect)
+        theta_l, cur = now, tg.cpu().numpy().astype(np.float64)
+    assert frozen_bytes_equal(cfg, m, weights, mask) == []
+    wd = m.get_weight("layers.1.wd", (cfg["d_ff"], cfg["d_model"]))
+    assert np.array_equal(wd.T, m.get_weight("shadow.layers.1.wd", (cfg["d_model"], cfg["d_ff"])))
+    # error paths
+    lib = pp.load_library()
+    bad = pp.PPOuter(0.7, 0.9, 1, 0.0)
+    import ctypes
+    assert lib.pp_outer_delta(m.h, tg.data_ptr(), mom.data_ptr(), None, ctypes.byref(bad), None) == -1
+    m.close()

@@ -83,3 +83,30 @@ def test_125m_fifty_steps_leave_frozen_parameters_bit_identical():
     wd_t = m.get_weight("shadow.layers.7.wd", (cfg["d_model"], cfg["d_ff"]))
     assert np.array_equal(wd.T, wd_t)
     m.close()
+
+
+def test_1p3b_shape_step_matches_oracle_on_one_sequence():
+    """The benchmark's own launch configuration (1.3B shape: 24 x 2048, 16 heads of 128, d_ff 8192, vocab 32000,
+    seq 2048, 1/32 FFN slice, MFMA kernels) on a one-sequence batch, against the full 24-layer fp64 oracle."""
+    cfg = gen.make_config("1p3b")
+    print("case 1p3b B=1", flush=True)
+    weights = gen.make_weights(cfg, seed=1234, threads=16)
+    mask = gen.ffn_slice_mask(cfg, 0, 32)
+    tok, tgt = gen.make_tokens(cfg, seed=1234, batch=1)
+    m = make_gpu_model(dict(cfg, batch=1), weights, mask)
+    td, gd = m.upload_tokens(tok, tgt)
+    loss_gpu = float(m.step(td, gd, HP).item())
+    g_gpu = m.get_state("g")
+    cnt = m.counters()
+    print("gpu step done", flush=True)
+    params = O.to_f64(weights)
+    loss_ref, cache = O.forward(cfg, params, tok, tgt)
+    print("oracle forward done", flush=True)
+    g_ref, info = O.backward_restricted(cfg, params, cache, mask)
+    assert abs(loss_gpu - loss_ref) <= 1e-2 * abs(loss_ref), (loss_gpu, loss_ref)
+    worst = min(cosine(g_gpu[off:off + n], g_ref[off:off + n]) for _, off, n in segment_slices(cfg, mask))
+    print(f"loss gpu {loss_gpu:.5f} oracle {loss_ref:.5f}; worst per-tensor gradient cosine {worst:.6f}", flush=True)
+    assert worst >= 0.999
+    assert cnt["flops_fwd"] + cnt["flops_bwd"] == O.flops_forward(cfg, 1, 2048) + info["flops_bwd"]
+    assert frozen_bytes_equal(cfg, m, weights, mask) == []
+    m.close()

@@ -64,7 +64,11 @@ static void head_transpose(hipStream_t st, const void* src, int ld_src, int col0
 }
 
 // ------------------------------------------------------------------------------------------ tile staging helpers
-// A tile is ROWS x (CPR 16-byte chunks); chunk c of row r lives at r*CPR + (c ^ (r & 7)).  256 threads.
+// A tile is ROWS x (CPR 16-byte chunks); chunk c of row r lives at r*CPR + (c ^ swz<CPR>(r)).  The swizzle makes the
+// 16 rows touched together by a 16-byte fragment read (same logical chunk) cover all 64 LDS banks once: with 128-byte
+// rows (CPR 8) rows r, r+1 differ in address bit 7 and (r >> 1) & 7 spreads the chunk; with 256-byte rows (CPR 16)
+// the row does not enter the bank index, so r & 15 spreads the chunk.  256 threads.
+template <int CPR> __device__ __forceinline__ int swz(int r) { return CPR == 8 ? ((r >> 1) & 7) : (r & 15); }
 template <int ROWS, int CPR>
 struct Stage {
   static constexpr int N = ROWS * CPR / 256;
@@ -81,13 +85,13 @@ struct Stage {
     for (int i = 0; i < N; ++i) {
       const int q = threadIdx.x + 256 * i;
       const int row = q / CPR, c = q % CPR;
-      tile[row * CPR + (c ^ (row & 7))] = reg[i];
+      tile[row * CPR + (c ^ swz<CPR>(row))] = reg[i];
     }
   }
 };
 template <int CPR>
 __device__ __forceinline__ bf16x8 frag(const u32x4* tile, int row, int chunk) {
-  return __builtin_bit_cast(bf16x8, tile[row * CPR + (chunk ^ (row & 7))]);
+  return __builtin_bit_cast(bf16x8, tile[row * CPR + (chunk ^ swz<CPR>(row))]);
 }
 
 constexpr float LOG2E = 1.4426950408889634f, LN2 = 0.6931471805599453f;

@@ -7,9 +7,11 @@
 // Tiling: 256 x 256 output tile per workgroup of 512 threads = 8 wavefronts (2 per SIMD) arranged 2 (M) x 4 (N);
 // each wavefront owns 128 x 64 = 4 x 2 MFMA tiles of v_mfma_f32_32x32x16_bf16 (128 accumulator registers).
 // K advances in steps of 64: the A and B panels (256 x 64 bf16 each, 32 KB + 32 KB) are staged in LDS, two stages
-// (128 KB of the CU's 160 KB), global loads for step k+1 are in flight in registers while step k is multiplied.
-// LDS rows are 128 bytes = 8 chunks of 16 bytes; chunk c of row r is stored at chunk c ^ (r & 7) so that the
-// 16-byte fragment reads of 8 consecutive rows fall into distinct banks.
+// (128 KB of the CU's 160 KB); global loads run two K steps ahead in registers (see the staging comment below).
+// LDS rows are 128 bytes = 8 chunks of 16 bytes; chunk c of row r is stored at chunk c ^ ((r >> 1) & 7): a 16-byte
+// fragment read is served 16 lanes (= 16 consecutive rows, same logical chunk) at a time, and with this swizzle those
+// 16 addresses cover all 64 four-byte banks exactly once (rows r and r+1 differ in address bit 7, rows r and r+2k in
+// the chunk).
 // Workgroup ids are remapped so that the workgroups resident on one XCD (ids equal mod 8) work on neighbouring
 // tiles (shared A / B panels hit that XCD's L2), in groups of 8 M-tiles by all N-tiles.
 #include "pp_kernels.h"
@@ -48,7 +50,9 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_kernel(const bf16_t* __restr
   const int z = blockIdx.y;
   const size_t kbase = (size_t)z * Ksplit;
 
-  // ---- global -> register -> LDS staging: each thread moves 4 chunks of A and 4 chunks of B per K step
+  // ---- global -> register -> LDS staging: each thread moves 4 chunks of A and 4 chunks of B per K step.
+  // Two register sets: the loads for K step kt+2 are issued while step kt is multiplied (an L2 miss then has two
+  // steps to land), and the set holding step kt+1 is written to the free LDS stage in between the MFMA groups.
   const int lrow = tid >> 3, lc = tid & 7;
   const bf16_t* gA[4];
   const bf16_t* gB[4];
@@ -58,13 +62,17 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_kernel(const bf16_t* __restr
     const int row = lrow + 64 * i;
     gA[i] = A + (size_t)min(m0 + row, M - 1) * lda + kbase + lc * 8;
     gB[i] = B + (size_t)min(n0 + row, N - 1) * ldb + kbase + lc * 8;
-    sOff[i] = row * 8 + (lc ^ (row & 7));
+    sOff[i] = row * 8 + (lc ^ ((row >> 1) & 7));
   }
-  u32x4 ra[4], rb[4];
+  const int nk = Ksplit / BK;
+  u32x4 r0a[4], r0b[4], r1a[4], r1b[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) { ra[i] = *reinterpret_cast<const u32x4*>(gA[i]); rb[i] = *reinterpret_cast<const u32x4*>(gB[i]); }
+  for (int i = 0; i < 4; ++i) { r0a[i] = *reinterpret_cast<const u32x4*>(gA[i]); r0b[i] = *reinterpret_cast<const u32x4*>(gB[i]); }
+  const size_t k1 = (size_t)min(1, nk - 1) * BK;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) { lds[sOff[i]] = ra[i]; lds[BM * 8 + sOff[i]] = rb[i]; }
+  for (int i = 0; i < 4; ++i) { r1a[i] = *reinterpret_cast<const u32x4*>(gA[i] + k1); r1b[i] = *reinterpret_cast<const u32x4*>(gB[i] + k1); }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { lds[sOff[i]] = r0a[i]; lds[BM * 8 + sOff[i]] = r0b[i]; }
   __syncthreads();
 
   f32x16 acc[4][2];
@@ -75,38 +83,49 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_kernel(const bf16_t* __restr
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int l32 = lane & 31, lhi = lane >> 5, sw = lane & 7;
+  const int l32 = lane & 31, lhi = lane >> 5, sw = (lane >> 1) & 7;
   const int aRow = (wm * 128 + l32) * 8, bRow = BM * 8 + (wn * 64 + l32) * 8;
-  const int nk = Ksplit / BK;
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = (kt & 1) * STAGE_CHUNKS, nxt = ((kt + 1) & 1) * STAGE_CHUNKS;
-    // prefetch the next K step into registers (the last iteration re-reads its own step; the copy it then
-    // stores lands in the stage nobody reads again)
-    const size_t knext = (size_t)min(kt + 1, nk - 1) * BK;
+  auto kstep = [&](int cur, int s) {          // one 16-deep slice of the staged panels: 6 fragment reads, 8 MFMAs
+    const int pc = (2 * s + lhi) ^ sw;
+    bf16x8 af[4], bfr[2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      ra[i] = *reinterpret_cast<const u32x4*>(gA[i] + knext);
-      rb[i] = *reinterpret_cast<const u32x4*>(gB[i] + knext);
-    }
-    __builtin_amdgcn_sched_barrier(0);          // keep the prefetch ahead of the multiply phase
+    for (int i = 0; i < 4; ++i) af[i] = __builtin_bit_cast(bf16x8, lds[cur + aRow + i * 32 * 8 + pc]);
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      const int pc = (2 * s + lhi) ^ sw;
-      bf16x8 af[4], bfr[2];
+    for (int j = 0; j < 2; ++j) bfr[j] = __builtin_bit_cast(bf16x8, lds[cur + bRow + j * 32 * 8 + pc]);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) af[i] = __builtin_bit_cast(bf16x8, lds[cur + aRow + i * 32 * 8 + pc]);
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j) bfr[j] = __builtin_bit_cast(bf16x8, lds[cur + bRow + j * 32 * 8 + pc]);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) { lds[nxt + sOff[i]] = ra[i]; lds[nxt + BM * 8 + sOff[i]] = rb[i]; }
-    __syncthreads();
+      for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+  };
+  // One K step: multiply step kt from stage kt&1; load step kt+2 into (la, lb); write step kt+1, held in (wa, wb), to
+  // the other stage.  Past the end the loads re-read the last step and the writes land in a stage nobody reads again.
+#define PP_GEMM_ITER(kt, la, lb, wa, wb)                                                              \
+  {                                                                                                   \
+    const int cur = ((kt) & 1) * STAGE_CHUNKS, nxt = (((kt) + 1) & 1) * STAGE_CHUNKS;                 \
+    const size_t k2 = (size_t)min((kt) + 2, nk - 1) * BK;                                             \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                   \
+      la[i] = *reinterpret_cast<const u32x4*>(gA[i] + k2);                                            \
+      lb[i] = *reinterpret_cast<const u32x4*>(gB[i] + k2);                                            \
+    }                                                                                                 \
+    __builtin_amdgcn_sched_barrier(0);                                                                \
+    kstep(cur, 0);                                                                                    \
+    __builtin_amdgcn_sched_barrier(0);                                                                \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) lds[nxt + sOff[i]] = wa[i];                         \
+    kstep(cur, 1);                                                                                    \
+    __builtin_amdgcn_sched_barrier(0);                                                                \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) lds[nxt + BM * 8 + sOff[i]] = wb[i];                \
+    kstep(cur, 2);                                                                                    \
+    __builtin_amdgcn_sched_barrier(0);                                                                \
+    kstep(cur, 3);                                                                                    \
+    __syncthreads();                                                                                  \
   }
+  int kt = 0;
+  for (; kt + 1 < nk; kt += 2) {
+    PP_GEMM_ITER(kt, r0a, r0b, r1a, r1b)
+    PP_GEMM_ITER(kt + 1, r1a, r1b, r0a, r0b)
+  }
+  if (kt < nk) PP_GEMM_ITER(kt, r0a, r0b, r1a, r1b)
+#undef PP_GEMM_ITER
 
   // ---- epilogue: accumulator element r of MFMA tile (i, j) is row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
   const int col_base = n0 + wn * 64 + l32;

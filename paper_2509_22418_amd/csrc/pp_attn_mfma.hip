@@ -25,7 +25,9 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
 
-__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) { return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16); }
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) { return f32x2_to_bf16x2(a, b); }
+// raw v_exp_f32: inputs here are <= 0 (or -inf); results below the normal range flush to zero, which is what softmax wants
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ bf16x8 pack8(const f32x16& v, int base) {
   u32x4 w;
   w[0] = pack_bf16x2(v[base + 0], v[base + 1]);
@@ -165,12 +167,12 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
       tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
       const float m_new = fmaxf(m_run, tmax);
       const float m_use = (m_new == -INFINITY) ? 0.f : m_new;          // whole row masked so far (only for padded queries)
-      const float alpha = exp2f(m_run - m_use);
+      const float alpha = fast_exp2(m_run - m_use);
       float psum = 0.f;
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { const float p = exp2f(sacc[mt][r] - m_use); sacc[mt][r] = p; psum += p; }
+        for (int r = 0; r < 16; ++r) { const float p = fast_exp2(sacc[mt][r] - m_use); sacc[mt][r] = p; psum += p; }
       l_run = l_run * alpha + psum;
       m_run = m_new;
 #pragma unroll
@@ -280,7 +282,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(const bf16_t* __res
       for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          float p = exp2f(sacc[mt][r] * sc2 - lse2);
+          float p = fast_exp2(sacc[mt][r] * sc2 - lse2);
           if (diag) { const int key = kv0 + mt * 32 + 8 * (r >> 2) + 4 * lh + (r & 3); if (key > q) p = 0.f; }
           sacc[mt][r] = p * (dpacc[mt][r] - Dq);
         }
@@ -415,7 +417,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const bf16_t* __re
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int r = 4 * g + e;
-            float p = exp2f(sacc[mt][r] * sc2 - ls[e]);
+            float p = fast_exp2(sacc[mt][r] * sc2 - ls[e]);
             if (edge) { const int qq = qq0 + rowb + e; if (key > qq || qq >= S) p = 0.f; }
             pacc[mt][r] = p;
             sacc[mt][r] = p * (dpacc[mt][r] - ds[e]);

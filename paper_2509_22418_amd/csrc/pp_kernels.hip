@@ -621,8 +621,8 @@ template <class T> __device__ __forceinline__ void store4(T* dst, float4 v);
 template <> __device__ __forceinline__ void store4<float>(float* dst, float4 v) { *reinterpret_cast<float4*>(dst) = v; }
 template <> __device__ __forceinline__ void store4<bf16_t>(bf16_t* dst, float4 v) {
   uint2 w;
-  w.x = (uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16);
-  w.y = (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16);
+  w.x = f32x2_to_bf16x2(v.x, v.y);
+  w.y = f32x2_to_bf16x2(v.z, v.w);
   *reinterpret_cast<uint2*>(dst) = w;
 }
 

@@ -318,8 +318,10 @@ extern "C" int pp_init_model(const pp_config* cfg, void* params_dev, size_t para
 extern "C" void pp_free(pp_model* m) { delete m; }
 
 extern "C" int pp_set_option(pp_model* m, const char* key, int64_t value) {
+  if (key && !strcmp(key, "gemm_variant")) { gemm_set_variant((int)value); return PP_OK; }          // process-wide, no model needed
   if (!m || !key) return fail(PP_EINVAL, "pp_set_option: NULL");
   if (!strcmp(key, "force_plain")) { m->force_plain = value != 0; return PP_OK; }
+  if (!strcmp(key, "gemm_variant")) { gemm_set_variant((int)value); return PP_OK; }
   if (!strcmp(key, "time_gemm")) {
     if (hipStreamSynchronize(m->st) != hipSuccess) return fail(PP_EHIP, "pp_set_option: stream sync failed");
     m->time_gemm = value != 0; m->ev_used = 0; m->timed_flops = 0;

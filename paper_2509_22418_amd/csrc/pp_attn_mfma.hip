@@ -395,19 +395,18 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const bf16_t* __re
     load_stat(qqn);
     __builtin_amdgcn_sched_barrier(0);
     if (qq0 + 63 >= kw0) {          // wave-uniform: some query of the tile sees some key of this wave
-      f32x16 sacc[2], dpacc[2];
-      zero16(sacc[0]); zero16(sacc[1]); zero16(dpacc[0]); zero16(dpacc[1]);
-#pragma unroll
-      for (int s = 0; s < KS; ++s)
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
-          sacc[mt] = MFMA(frag<CPRK>(qtile, mt * 32 + l32, 2 * s + lh), kf[s], sacc[mt]);
-          dpacc[mt] = MFMA(frag<CPRK>(dotile, mt * 32 + l32, 2 * s + lh), vf[s], dpacc[mt]);
-        }
       const bool edge = (qq0 < kw0 + 31) || (qq0 + 63 >= S);          // causal boundary or padded queries inside the tile
-      f32x16 pacc[2];
+      // the 64 queries of the tile are processed as two groups of 32 to keep the score-shaped registers small
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
+      for (int mt = 0; mt < 2; ++mt) {
+        if (qq0 + 32 * mt + 31 < kw0) continue;          // wave-uniform: this group lies entirely above the diagonal
+        f32x16 sacc, dpacc, pacc;
+        zero16(sacc); zero16(dpacc);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+          sacc = MFMA(frag<CPRK>(qtile, mt * 32 + l32, 2 * s + lh), kf[s], sacc);
+          dpacc = MFMA(frag<CPRK>(dotile, mt * 32 + l32, 2 * s + lh), vf[s], dpacc);
+        }
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const int rowb = mt * 32 + 8 * g + 4 * lh;          // 4 consecutive query rows of this lane
@@ -417,22 +416,23 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const bf16_t* __re
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int r = 4 * g + e;
-            float p = fast_exp2(sacc[mt][r] * sc2 - ls[e]);
+            float p = fast_exp2(sacc[r] * sc2 - ls[e]);
             if (edge) { const int qq = qq0 + rowb + e; if (key > qq || qq >= S) p = 0.f; }
-            pacc[mt][r] = p;
-            sacc[mt][r] = p * (dpacc[mt][r] - ds[e]);
+            pacc[r] = p;
+            sacc[r] = p * (dpacc[r] - ds[e]);
           }
         }
-      bf16x8 pf[4], dsf[4];
+        bf16x8 pf[2], dsf[2];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) { pf[u] = pack8(pacc[u >> 1], 8 * (u & 1)); dsf[u] = pack8(sacc[u >> 1], 8 * (u & 1)); }
+        for (int u = 0; u < 2; ++u) { pf[u] = pack8(pacc, 8 * u); dsf[u] = pack8(sacc, 8 * u); }
 #pragma unroll
-      for (int c = 0; c < CT; ++c)
+        for (int c = 0; c < CT; ++c)
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          dvacc[c] = MFMA(frag<8>(dottile, c * 32 + l32, 2 * u + lh), pf[u], dvacc[c]);
-          dkacc[c] = MFMA(frag<8>(qttile, c * 32 + l32, 2 * u + lh), dsf[u], dkacc[c]);
-        }
+          for (int u = 0; u < 2; ++u) {
+            dvacc[c] = MFMA(frag<8>(dottile, c * 32 + l32, 2 * (2 * mt + u) + lh), pf[u], dvacc[c]);
+            dkacc[c] = MFMA(frag<8>(qttile, c * 32 + l32, 2 * (2 * mt + u) + lh), dsf[u], dkacc[c]);
+          }
+      }
     }
     __builtin_amdgcn_sched_barrier(0);
     store_all(nxt);

@@ -163,6 +163,180 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_kernel(const bf16_t* __restr
   }
 }
 
+
+// ------------------------------------------------------------------------------------------ direct-to-LDS variant
+// Same 256 x 256 tile and wave layout, but the panels go from global memory straight into LDS
+// (global_load_lds_dwordx4: lane l's 16 bytes land at M0 base + 16 l), no staging registers and no LDS write
+// instructions.  K advances in steps of 32 through FOUR 32 KB stages, so the loads of step kt+3 are issued while
+// step kt is multiplied.  LDS rows are 64 bytes = 4 chunks; a wave-load fills 16 consecutive rows; chunk c of row r
+// sits at chunk c ^ ((r >> 2) & 3) (the permutation is applied on the source side), which spreads the 16 rows of a
+// fragment read over all 64 banks.
+constexpr int DL_BK = 32, DL_STAGES = 4;
+constexpr int DL_STAGE_CHUNKS = (BM + BN) * 4;
+constexpr int DL_LDS_BYTES = DL_STAGES * DL_STAGE_CHUNKS * 16;
+#define PP_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
+#define PP_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+template <int EPI, bool OUT_F32>
+__global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ B, int ldb,
+                                                               void* Cv, int ldc, int M, int N, int Ksplit, const bf16_t* __restrict__ R,
+                                                               int tiles_m, int tiles_n) {
+  extern __shared__ u32x4 lds[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 2, wn = wave & 3;
+  const int nb = tiles_m * tiles_n;
+  int pid = blockIdx.x;
+  if ((nb & 7) == 0) pid = (pid & 7) * (nb >> 3) + (pid >> 3);
+  constexpr int GROUP = 8;
+  const int per_group = GROUP * tiles_n;
+  const int group = pid / per_group;
+  const int first_m = group * GROUP;
+  const int gsz = min(tiles_m - first_m, GROUP);
+  const int in_group = pid - group * per_group;
+  const int tm = first_m + in_group % gsz, tn = in_group / gsz;
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int z = blockIdx.y;
+  const size_t kbase = (size_t)z * Ksplit;
+
+  // wave w fills row groups 2w and 2w+1 (16 rows each) of the A panel and of the B panel
+  const bf16_t* gsrc[4];
+  int ldst[4];          // chunk offset of the row group inside a stage (wave-uniform)
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int grp = wave * 2 + i;
+    const int row = grp * 16 + (lane >> 2);
+    const int c = (lane & 3) ^ ((row >> 2) & 3);
+    gsrc[i] = A + (size_t)min(m0 + row, M - 1) * lda + kbase + c * 8;
+    gsrc[2 + i] = B + (size_t)min(n0 + row, N - 1) * ldb + kbase + c * 8;
+    ldst[i] = grp * 64;
+    ldst[2 + i] = BM * 4 + grp * 64;
+  }
+  const int nk = Ksplit / DL_BK;
+  auto issue = [&](int kt) {          // loads of K step kt (clamped) into stage kt % 4
+    const int ktc = min(kt, nk - 1);
+    u32x4* stage = lds + (kt & (DL_STAGES - 1)) * DL_STAGE_CHUNKS;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_global_load_lds(PP_GPTR(gsrc[i] + (size_t)ktc * DL_BK), PP_LPTR(stage + ldst[i]), 16, 0, 0);
+  };
+  issue(0); issue(1); issue(2);
+  // Plain s_barrier (no fence): a workgroup fence would force vmcnt(0), i.e. wait for ALL loads in flight.  The only
+  // LDS traffic here is DMA writes (tracked by vmcnt) and fragment reads (consumed by MFMAs before the barrier).
+  __builtin_amdgcn_s_waitcnt(0x0F70 | 8);          // vmcnt(8): step 0 has landed (steps 1, 2 may be in flight)
+  __builtin_amdgcn_s_barrier();
+
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int l32 = lane & 31, lhi = lane >> 5, sw = (l32 >> 2) & 3;
+  const int aRow = (wm * 128 + l32) * 4, bRow = BM * 4 + (wn * 64 + l32) * 4;
+  // Fragment registers are double-buffered: the reads of the next 16-deep slice are issued before the MFMAs of the
+  // current one, so LDS latency hides behind matrix work inside one wavefront.
+  bf16x8 fa[2][4], fb[2][2];
+  auto readf = [&](int buf, int stage_off, int s) {
+    const int pc = (2 * s + lhi) ^ sw;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) fa[buf][i] = __builtin_bit_cast(bf16x8, lds[stage_off + aRow + i * 32 * 4 + pc]);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) fb[buf][j] = __builtin_bit_cast(bf16x8, lds[stage_off + bRow + j * 32 * 4 + pc]);
+  };
+  auto mm = [&](int buf, int half) {          // 4 of the slice's 8 MFMAs
+#pragma unroll
+    for (int i = 2 * half; i < 2 * half + 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
+  };
+  readf(0, 0, 0);
+  for (int kt = 0; kt < nk; ++kt) {
+    const int cur = (kt & (DL_STAGES - 1)) * DL_STAGE_CHUNKS, nxt = ((kt + 1) & (DL_STAGES - 1)) * DL_STAGE_CHUNKS;
+    issue(kt + 3);
+    __builtin_amdgcn_sched_barrier(0);
+    // slice 0 of step kt multiplies while slice 1 is read: one fragment read is slotted behind each of the first six
+    // MFMAs (the in-order LDS counter then never makes this slice's MFMAs wait for the next slice's reads)
+    readf(1, cur, 1);
+    mm(0, 0);
+    mm(0, 1);
+#pragma unroll
+    for (int g = 0; g < 6; ++g) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);          // 1 MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);          // 1 DS read
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    // vmcnt(8): step kt+1 has landed in this wave's row groups; lgkmcnt(0): this wave's reads of stage kt % 4 are done
+    __builtin_amdgcn_s_waitcnt(0x0070 | 8);
+    __builtin_amdgcn_s_barrier();                    // everybody's step kt+1 is in LDS; stage kt % 4 may be refilled
+    readf(0, nxt, 0);
+    mm(1, 0);
+    mm(1, 1);
+#pragma unroll
+    for (int g = 0; g < 6; ++g) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 1);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);              // drain the clamped tail loads before the LDS is released
+
+  const int col_base = n0 + wn * 64 + l32;
+  const int row_base = m0 + wm * 128 + 4 * lhi;
+  if constexpr (OUT_F32) {
+    float* C = reinterpret_cast<float*>(Cv) + (size_t)z * (size_t)M * (size_t)ldc;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int col = col_base + j * 32;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
+          if (row < M && col < N) C[(size_t)row * ldc + col] = acc[i][j][r];
+        }
+      }
+  } else {
+    bf16_t* C = reinterpret_cast<bf16_t*>(Cv);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int col = col_base + j * 32;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
+          if (row < M && col < N) {
+            float v = acc[i][j][r];
+            if constexpr (EPI == EPI_ADD_RES) v += to_f32(R[(size_t)row * ldc + col]);
+            C[(size_t)row * ldc + col] = from_f32<bf16_t>(v);
+          }
+        }
+      }
+  }
+}
+
+static int g_gemm_variant = 1;          // 0: register-staged kernel, 1: direct-to-LDS kernel (default: faster on every shape measured)
+void gemm_set_variant(int v) { g_gemm_variant = v; }
+
+template <int EPI, bool OUT_F32>
+static int launch_dl(hipStream_t st, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int Ksplit, const void* R, int splits) {
+  static bool attr_done = false;
+  auto kern = gemm_nt_mfma_dl_kernel<EPI, OUT_F32>;
+  if (!attr_done) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, DL_LDS_BYTES) != hipSuccess) return 1;
+    attr_done = true;
+  }
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  dim3 grid(tiles_m * tiles_n, splits);
+  kern<<<grid, 512, DL_LDS_BYTES, st>>>((const bf16_t*)A, lda, (const bf16_t*)B, ldb, C, ldc, M, N, Ksplit, (const bf16_t*)R, tiles_m, tiles_n);
+  return 0;
+}
+
 template <int EPI, bool OUT_F32>
 static int launch(hipStream_t st, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int Ksplit, const void* R, int splits) {
   static bool attr_done = false;          // one-time opt-in to > 64 KB of dynamic LDS for this instantiation
@@ -171,6 +345,7 @@ static int launch(hipStream_t st, const void* A, int lda, const void* B, int ldb
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES) != hipSuccess) return 1;
     attr_done = true;
   }
+  if (g_gemm_variant == 1) return launch_dl<EPI, OUT_F32>(st, A, lda, B, ldb, C, ldc, M, N, Ksplit, R, splits);
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   dim3 grid(tiles_m * tiles_n, splits);
   kern<<<grid, 512, GEMM_LDS_BYTES, st>>>((const bf16_t*)A, lda, (const bf16_t*)B, ldb, C, ldc, M, N, Ksplit, (const bf16_t*)R, tiles_m, tiles_n);

@@ -67,6 +67,7 @@ void k_synth_delta_sum(hipStream_t st, float* dst, size_t n, const uint64_t* key
 // MFMA paths (bf16 only).  Return 0 if launched, 1 if the shape is not supported (caller falls back).
 int k_gemm_nt_mfma(hipStream_t st, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
                    int epi, const void* R, int out_f32, int splits, float* partial);
+void gemm_set_variant(int v);          // 0: register-staged MFMA GEMM, 1: direct-to-LDS MFMA GEMM
 // scratch: 3 * attn_scratch_elems(B, S, h, dh) bf16 elements for the attention-transposed operand copies.
 size_t attn_scratch_elems(int B, int S, int h, int dh);
 int k_attn_fwd_mfma(hipStream_t st, const void* qkv, void* o, float* lse, void* scratch, int B, int S, int h, int dh);

@@ -37,9 +37,12 @@ GEMM_CASES = [
 ]
 
 
+@pytest.mark.parametrize("variant", [0, 1])
 @pytest.mark.parametrize("M,N,K,res,f32,splits", GEMM_CASES)
-def test_gemm_nt_matches_definition(M, N, K, res, f32, splits):
-    print(f"case gemm {M}x{N}x{K} res={res} f32={f32} splits={splits}", flush=True)
+def test_gemm_nt_matches_definition(M, N, K, res, f32, splits, variant):
+    """variant 0: register-staged MFMA kernel; 1: direct-to-LDS MFMA kernel."""
+    print(f"case gemm {M}x{N}x{K} res={res} f32={f32} splits={splits} variant={variant}", flush=True)
+    pp.pp_set_option(None, "gemm_variant", variant)
     Ad, A = dev_bf16(rnd((M, K), 1))
     Bd, B = dev_bf16(rnd((N, K), 2))
     ref = A @ B.T

@@ -71,26 +71,32 @@ static void head_transpose(hipStream_t st, const void* src, int ld_src, int col0
 // rows (CPR 8) rows r, r+1 differ in address bit 7 and (r >> 1) & 7 spreads the chunk; with 256-byte rows (CPR 16)
 // the row does not enter the bank index, so r & 15 spreads the chunk.  256 threads.
 template <int CPR> __device__ __forceinline__ int swz(int r) { return CPR == 8 ? ((r >> 1) & 7) : (r & 15); }
-template <int ROWS, int CPR>
+#define PP_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
+#define PP_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
+// Tiles go from global memory straight into LDS (global_load_lds_dwordx4: the 64 lanes' 16-byte pieces land at
+// consecutive LDS addresses from a wave-uniform base), so one wave-load fills 64 / CPR consecutive rows and the swizzle
+// is applied by choosing which source chunk each lane fetches.  No staging registers, no LDS write instructions.
+// Completion is tracked by vmcnt; callers wait for it and then cross a plain s_barrier.
+template <int ROWS, int CPR, int NW = 4>
 struct Stage {
-  static constexpr int N = ROWS * CPR / 256;
+  static constexpr int N = ROWS * CPR / (64 * NW);          // wave-loads per wave (NW waves in the workgroup)
   template <class F>
-  static __device__ __forceinline__ void load(u32x4 (&reg)[N], F&& src_of) {          // src_of(row, chunk) -> const bf16_t*
+  static __device__ __forceinline__ void issue(u32x4* tile, int wave, int lane, F&& src_of) {          // src_of(row, chunk) -> const bf16_t*
+    constexpr int RPL = 64 / CPR;          // rows per wave-load
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-      const int q = threadIdx.x + 256 * i;
-      reg[i] = *reinterpret_cast<const u32x4*>(src_of(q / CPR, q % CPR));
-    }
-  }
-  static __device__ __forceinline__ void store(const u32x4 (&reg)[N], u32x4* tile) {
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-      const int q = threadIdx.x + 256 * i;
-      const int row = q / CPR, c = q % CPR;
-      tile[row * CPR + (c ^ swz<CPR>(row))] = reg[i];
+      const int w = wave * N + i;
+      const int row = w * RPL + lane / CPR;
+      const int c = (lane % CPR) ^ swz<CPR>(row);
+      __builtin_amdgcn_global_load_lds(PP_GPTR(src_of(row, c)), PP_LPTR(tile + w * 64), 16, 0, 0);
     }
   }
 };
+// wait for this wave's DMA loads (vmcnt 0) and LDS reads (lgkmcnt 0), then meet the other waves
+__device__ __forceinline__ void stage_sync() {
+  __builtin_amdgcn_s_waitcnt(0x0070);
+  __builtin_amdgcn_s_barrier();
+}
 template <int CPR>
 __device__ __forceinline__ bf16x8 frag(const u32x4* tile, int row, int chunk) {
   return __builtin_bit_cast(bf16x8, tile[row * CPR + (chunk ^ swz<CPR>(row))]);
@@ -109,7 +115,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
   const int d = h * DH, ld = 3 * d;
   const int qblk = gridDim.x - 1 - blockIdx.x;          // heaviest (latest) query blocks first
   const int head = blockIdx.y, b = blockIdx.z;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lh = lane >> 5;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), l32 = lane & 31, lh = lane >> 5;
   const int q0 = qblk * 128, qw0 = q0 + wave * 32;
   const int q = qw0 + l32;
   const bf16_t* base = qkv + (size_t)b * S * ld + (size_t)head * DH;
@@ -128,22 +134,19 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
   float m_run = -INFINITY, l_run = 0.f;
   const float sc2 = LOG2E / sqrtf((float)DH);
 
-  u32x4 rk[Stage<64, CPRK>::N], rv[Stage<DH, 8>::N];
   auto ksrc = [&](int kv0) { return [=](int row, int c) { return base + (size_t)min(kv0 + row, S - 1) * ld + d + c * 8; }; };
   auto vsrc = [&](int kv0) { return [=](int row, int c) { return vtb + (size_t)row * Sp + kv0 + c * 8; }; };
-  Stage<64, CPRK>::load(rk, ksrc(0));
-  Stage<DH, 8>::load(rv, vsrc(0));
-  Stage<64, CPRK>::store(rk, lds);
-  Stage<DH, 8>::store(rv, lds + K_CH);
-  __syncthreads();
+  Stage<64, CPRK>::issue(lds, wave, lane, ksrc(0));
+  Stage<DH, 8>::issue(lds + K_CH, wave, lane, vsrc(0));
+  stage_sync();
 
   for (int j = 0; j < n_tiles; ++j) {
     const u32x4* kt = lds + (j & 1) * ST_CH;
     const u32x4* vtile = kt + K_CH;
     u32x4* nxt = lds + ((j + 1) & 1) * ST_CH;
     const int kv0 = j * 64, kvn = min(j + 1, n_tiles - 1) * 64;
-    Stage<64, CPRK>::load(rk, ksrc(kvn));
-    Stage<DH, 8>::load(rv, vsrc(kvn));
+    Stage<64, CPRK>::issue(nxt, wave, lane, ksrc(kvn));
+    Stage<DH, 8>::issue(nxt + K_CH, wave, lane, vsrc(kvn));
     __builtin_amdgcn_sched_barrier(0);
     if (kv0 <= qw0 + 31) {          // wave-uniform: some key of the tile is visible to some query of this wave
       f32x16 sacc[2];
@@ -153,18 +156,23 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) sacc[mt] = MFMA(frag<CPRK>(kt, mt * 32 + l32, 2 * s + lh), qf[s], sacc[mt]);
       }
-      float tmax = -INFINITY;
-      const bool diag = kv0 + 63 > qw0;          // some (key, query) pair of the tile may be masked
+      float tmax = -INFINITY;          // row maximum of the raw scores (the scale is positive, so it commutes with max)
+      if (kv0 + 63 > qw0) {          // wave-uniform: some (key, query) pair of the tile is masked
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
+        for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float v = sacc[mt][r] * sc2;
-          if (diag) { const int key = kv0 + mt * 32 + 8 * (r >> 2) + 4 * lh + (r & 3); if (key > q) v = -INFINITY; }
-          sacc[mt][r] = v;
-          tmax = fmaxf(tmax, v);
-        }
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+          for (int r = 0; r < 16; ++r) {
+            const int key = kv0 + mt * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+            if (key > q) sacc[mt][r] = -INFINITY;
+            tmax = fmaxf(tmax, sacc[mt][r]);
+          }
+      } else {
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sacc[mt][r]);
+      }
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64)) * sc2;
       const float m_new = fmaxf(m_run, tmax);
       const float m_use = (m_new == -INFINITY) ? 0.f : m_new;          // whole row masked so far (only for padded queries)
       const float alpha = fast_exp2(m_run - m_use);
@@ -172,13 +180,15 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { const float p = fast_exp2(sacc[mt][r] - m_use); sacc[mt][r] = p; psum += p; }
+        for (int r = 0; r < 16; ++r) { const float p = fast_exp2(fmaf(sacc[mt][r], sc2, -m_use)); sacc[mt][r] = p; psum += p; }
       l_run = l_run * alpha + psum;
       m_run = m_new;
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {          // wave-uniform: some row maximum moved
 #pragma unroll
-      for (int c = 0; c < CT; ++c)
+        for (int c = 0; c < CT; ++c)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[c][r] *= alpha;
+          for (int r = 0; r < 16; ++r) oacc[c][r] *= alpha;
+      }
       bf16x8 pf[4];
 #pragma unroll
       for (int t = 0; t < 4; ++t) pf[t] = pack8(sacc[t >> 1], 8 * (t & 1));
@@ -188,9 +198,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
         for (int t = 0; t < 4; ++t) oacc[c] = MFMA(frag<8>(vtile, c * 32 + l32, 2 * t + lh), pf[t], oacc[c]);
     }
     __builtin_amdgcn_sched_barrier(0);
-    Stage<64, CPRK>::store(rk, nxt);
-    Stage<DH, 8>::store(rv, nxt + K_CH);
-    __syncthreads();
+    stage_sync();
   }
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   if (q < S) {
@@ -210,23 +218,25 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
 }
 
 // ------------------------------------------------------------------------------------------ backward: dQ
-// Same blocking as the forward.  Per KV tile: S^T = K Q^T, dP^T = V dO^T, dS^T = P^T * (dP^T - D), dQ^T += AT(K) dS^T.
+// grid (ceil(S/256), h, B), 512 threads = 8 waves (2 per SIMD, <= 256 registers each, so every MFMA keeps its
+// accumulator in ordinary VGPRs): wave w owns queries q0 + 32w .. +31.  Per KV tile of 64 keys, in two groups of 32:
+// S^T = K Q^T, dP^T = V dO^T, dS^T = P^T * (dP^T - D), dQ^T += AT(K) dS^T.
 template <int DH>
-__global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ kt_at,
+__global__ __launch_bounds__(512, 2) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ kt_at,
                                                               const bf16_t* __restrict__ dO, const float* __restrict__ lse,
                                                               const float* __restrict__ Dbuf, bf16_t* __restrict__ dqkv, int S, int Sp, int h) {
-  constexpr int KS = DH / 16, CT = DH / 32, CPRK = DH / 8;
+  constexpr int KS = DH / 16, CT = DH / 32, CPRK = DH / 8, NW = 8;
   extern __shared__ u32x4 lds[];
   constexpr int K_CH = 64 * CPRK, T_CH = DH * 8, ST_CH = 2 * K_CH + T_CH;
   const int d = h * DH, ld = 3 * d;
   const int qblk = gridDim.x - 1 - blockIdx.x;
   const int head = blockIdx.y, b = blockIdx.z;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lh = lane >> 5;
-  const int q0 = qblk * 128, qw0 = q0 + wave * 32;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), l32 = lane & 31, lh = lane >> 5;
+  const int q0 = qblk * 256, qw0 = q0 + wave * 32;
   const int q = qw0 + l32, qc = min(q, S - 1);
   const bf16_t* base = qkv + (size_t)b * S * ld + (size_t)head * DH;
   const bf16_t* ktb = kt_at + ((size_t)(b * h + head) * DH) * Sp;
-  const int n_tiles = min((q0 + 128 + 63) / 64, (S + 63) / 64);
+  const int n_tiles = min((q0 + 256 + 63) / 64, (S + 63) / 64);
   const float scale = 1.0f / sqrtf((float)DH), sc2 = LOG2E * scale;
 
   bf16x8 qf[KS], dof[KS];
@@ -240,22 +250,21 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(const bf16_t* __res
     }
   }
   const size_t stat = ((size_t)b * h + head) * S + qc;
-  const float lse2 = lse[stat] * LOG2E, Dq = Dbuf[stat];
+  const float nlse2 = -lse[stat] * LOG2E, Dq = Dbuf[stat];
   f32x16 dqacc[CT];
 #pragma unroll
   for (int c = 0; c < CT; ++c) zero16(dqacc[c]);
 
-  u32x4 rk[Stage<64, CPRK>::N], rv[Stage<64, CPRK>::N], rt[Stage<DH, 8>::N];
   auto ksrc = [&](int kv0) { return [=](int row, int c) { return base + (size_t)min(kv0 + row, S - 1) * ld + d + c * 8; }; };
   auto vsrc = [&](int kv0) { return [=](int row, int c) { return base + (size_t)min(kv0 + row, S - 1) * ld + 2 * d + c * 8; }; };
   auto tsrc = [&](int kv0) { return [=](int row, int c) { return ktb + (size_t)row * Sp + kv0 + c * 8; }; };
-  Stage<64, CPRK>::load(rk, ksrc(0));
-  Stage<64, CPRK>::load(rv, vsrc(0));
-  Stage<DH, 8>::load(rt, tsrc(0));
-  Stage<64, CPRK>::store(rk, lds);
-  Stage<64, CPRK>::store(rv, lds + K_CH);
-  Stage<DH, 8>::store(rt, lds + 2 * K_CH);
-  __syncthreads();
+  auto issue_all = [&](u32x4* stage, int kv0) {
+    Stage<64, CPRK, NW>::issue(stage, wave, lane, ksrc(kv0));
+    Stage<64, CPRK, NW>::issue(stage + K_CH, wave, lane, vsrc(kv0));
+    Stage<DH, 8, NW>::issue(stage + 2 * K_CH, wave, lane, tsrc(kv0));
+  };
+  issue_all(lds, 0);
+  stage_sync();
 
   for (int j = 0; j < n_tiles; ++j) {
     const u32x4* ktile = lds + (j & 1) * ST_CH;
@@ -263,42 +272,39 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(const bf16_t* __res
     const u32x4* ttile = ktile + 2 * K_CH;
     u32x4* nxt = lds + ((j + 1) & 1) * ST_CH;
     const int kv0 = j * 64, kvn = min(j + 1, n_tiles - 1) * 64;
-    Stage<64, CPRK>::load(rk, ksrc(kvn));
-    Stage<64, CPRK>::load(rv, vsrc(kvn));
-    Stage<DH, 8>::load(rt, tsrc(kvn));
+    issue_all(nxt, kvn);
     __builtin_amdgcn_sched_barrier(0);
-    if (kv0 <= qw0 + 31) {
-      f32x16 sacc[2], dpacc[2];
-      zero16(sacc[0]); zero16(sacc[1]); zero16(dpacc[0]); zero16(dpacc[1]);
 #pragma unroll
-      for (int s = 0; s < KS; ++s)
+    for (int mt = 0; mt < 2; ++mt) {
+      const int kg0 = kv0 + 32 * mt;
+      if (kg0 > qw0 + 31) continue;          // wave-uniform: every key of the group lies beyond every query of this wave
+      f32x16 sacc, dpacc;
+      zero16(sacc); zero16(dpacc);
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
-          sacc[mt] = MFMA(frag<CPRK>(ktile, mt * 32 + l32, 2 * s + lh), qf[s], sacc[mt]);
-          dpacc[mt] = MFMA(frag<CPRK>(vtile, mt * 32 + l32, 2 * s + lh), dof[s], dpacc[mt]);
-        }
-      const bool diag = kv0 + 63 > qw0;
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
+      for (int s = 0; s < KS; ++s) {
+        sacc = MFMA(frag<CPRK>(ktile, mt * 32 + l32, 2 * s + lh), qf[s], sacc);
+        dpacc = MFMA(frag<CPRK>(vtile, mt * 32 + l32, 2 * s + lh), dof[s], dpacc);
+      }
+      if (kg0 + 31 > qw0) {          // wave-uniform: the group straddles the diagonal
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          float p = fast_exp2(sacc[mt][r] * sc2 - lse2);
-          if (diag) { const int key = kv0 + mt * 32 + 8 * (r >> 2) + 4 * lh + (r & 3); if (key > q) p = 0.f; }
-          sacc[mt][r] = p * (dpacc[mt][r] - Dq);
+          const int key = kg0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+          const float p = key > q ? 0.f : fast_exp2(fmaf(sacc[r], sc2, nlse2));
+          sacc[r] = p * (dpacc[r] - Dq);
         }
-      bf16x8 dsf[4];
+      } else {
 #pragma unroll
-      for (int t = 0; t < 4; ++t) dsf[t] = pack8(sacc[t >> 1], 8 * (t & 1));
+        for (int r = 0; r < 16; ++r) sacc[r] = fast_exp2(fmaf(sacc[r], sc2, nlse2)) * (dpacc[r] - Dq);
+      }
+      bf16x8 dsf[2];
+      dsf[0] = pack8(sacc, 0); dsf[1] = pack8(sacc, 8);
 #pragma unroll
       for (int c = 0; c < CT; ++c)
 #pragma unroll
-        for (int t = 0; t < 4; ++t) dqacc[c] = MFMA(frag<8>(ttile, c * 32 + l32, 2 * t + lh), dsf[t], dqacc[c]);
+        for (int u = 0; u < 2; ++u) dqacc[c] = MFMA(frag<8>(ttile, c * 32 + l32, 2 * (2 * mt + u) + lh), dsf[u], dqacc[c]);
     }
     __builtin_amdgcn_sched_barrier(0);
-    Stage<64, CPRK>::store(rk, nxt);
-    Stage<64, CPRK>::store(rv, nxt + K_CH);
-    Stage<DH, 8>::store(rt, nxt + 2 * K_CH);
-    __syncthreads();
+    stage_sync();
   }
   if (q < S) {
     bf16_t* op = dqkv + ((size_t)b * S + q) * ld + (size_t)head * DH + 4 * lh;
@@ -315,21 +321,24 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(const bf16_t* __res
 }
 
 // ------------------------------------------------------------------------------------------ backward: dK, dV
-// grid (ceil(S/128), h, B): wave w owns keys k0 + 32w .. +31 (lane column = key); query tiles of 64 from the diagonal on.
-// Per query tile: S = Q K^T, dP = dO V^T, P = exp(S - lse), dS = P * (dP - D); dV^T += AT(dO) P, dK^T += AT(Q) dS.
+// grid (ceil(S/128), h, B), 512 threads = 8 waves (2 per SIMD): waves w and w+4 own keys k0 + 32(w&3) .. +31 (lane
+// column = key) and each accumulates one half of the head dimension of dK and dV, so that every accumulator fits
+// in VGPRs; both recompute the score tile.  Query tiles of 64 (two groups of 32) from the diagonal on:
+// S = Q K^T, dP = dO V^T, P = exp(S - lse), dS = P * (dP - D); dV^T += AT(dO) P, dK^T += AT(Q) dS.
 template <int DH>
-__global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ qt_at,
+__global__ __launch_bounds__(512, 2) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ qt_at,
                                                                const bf16_t* __restrict__ dO, const bf16_t* __restrict__ dot_at,
                                                                const float* __restrict__ lse, const float* __restrict__ Dbuf,
                                                                bf16_t* __restrict__ dqkv, int S, int Sp, int h) {
-  constexpr int KS = DH / 16, CT = DH / 32, CPRK = DH / 8;
+  constexpr int KS = DH / 16, CT = DH / 32, CTH = CT / 2, CPRK = DH / 8, NW = 8;
   extern __shared__ u32x4 lds[];
   constexpr int Q_CH = 64 * CPRK, T_CH = DH * 8, ST_CH = 2 * Q_CH + 2 * T_CH + 32;          // + 64 lse and 64 D floats (32 chunks)
   const int d = h * DH, ld = 3 * d;
   const int kblk = blockIdx.x;          // earliest key blocks see the most queries: already first
   const int head = blockIdx.y, b = blockIdx.z;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lh = lane >> 5;
-  const int k0 = kblk * 128, kw0 = k0 + wave * 32;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), l32 = lane & 31, lh = lane >> 5;
+  const int chalf = wave >> 2;
+  const int k0 = kblk * 128, kw0 = k0 + (wave & 3) * 32;
   const int key = kw0 + l32, keyc = min(key, S - 1);
   const bf16_t* base = qkv + (size_t)b * S * ld + (size_t)head * DH;
   const bf16_t* qtb = qt_at + ((size_t)(b * h + head) * DH) * Sp;
@@ -350,34 +359,26 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const bf16_t* __re
       vf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(vp + 16 * s));
     }
   }
-  f32x16 dkacc[CT], dvacc[CT];
+  f32x16 dkacc[CTH], dvacc[CTH];
 #pragma unroll
-  for (int c = 0; c < CT; ++c) { zero16(dkacc[c]); zero16(dvacc[c]); }
+  for (int c = 0; c < CTH; ++c) { zero16(dkacc[c]); zero16(dvacc[c]); }
 
-  u32x4 rq[Stage<64, CPRK>::N], rdo[Stage<64, CPRK>::N], rqt[Stage<DH, 8>::N], rdot[Stage<DH, 8>::N];
-  float rstat = 0.f;          // threads 0..63: lse of query row tid; 64..127: D of query row tid-64
   auto qsrc = [&](int qq0) { return [=](int row, int c) { return base + (size_t)min(qq0 + row, S - 1) * ld + c * 8; }; };
   auto dosrc = [&](int qq0) { return [=](int row, int c) { return dob + (size_t)min(qq0 + row, S - 1) * d + c * 8; }; };
   auto qtsrc = [&](int qq0) { return [=](int row, int c) { return qtb + (size_t)row * Sp + qq0 + c * 8; }; };
   auto dotsrc = [&](int qq0) { return [=](int row, int c) { return dotb + (size_t)row * Sp + qq0 + c * 8; }; };
-  auto load_stat = [&](int qq0) {
-    if (threadIdx.x < 64) rstat = lseb[min(qq0 + (int)threadIdx.x, S - 1)] * LOG2E;
-    else if (threadIdx.x < 128) rstat = Db[min(qq0 + (int)threadIdx.x - 64, S - 1)];
+  auto issue_all = [&](u32x4* stage, int qq0) {
+    Stage<64, CPRK, NW>::issue(stage, wave, lane, qsrc(qq0));
+    Stage<64, CPRK, NW>::issue(stage + Q_CH, wave, lane, dosrc(qq0));
+    Stage<DH, 8, NW>::issue(stage + 2 * Q_CH, wave, lane, qtsrc(qq0));
+    Stage<DH, 8, NW>::issue(stage + 2 * Q_CH + T_CH, wave, lane, dotsrc(qq0));
+    // per-row statistics: wave 0 brings the 64 log-sum-exps, wave 1 the 64 D values (4-byte pieces, lane l -> float l)
+    float* st = reinterpret_cast<float*>(stage + 2 * Q_CH + 2 * T_CH);
+    if (wave == 0) __builtin_amdgcn_global_load_lds(PP_GPTR(lseb + min(qq0 + lane, S - 1)), PP_LPTR(st), 4, 0, 0);
+    if (wave == 1) __builtin_amdgcn_global_load_lds(PP_GPTR(Db + min(qq0 + lane, S - 1)), PP_LPTR(st + 64), 4, 0, 0);
   };
-  auto store_all = [&](u32x4* stage) {
-    Stage<64, CPRK>::store(rq, stage);
-    Stage<64, CPRK>::store(rdo, stage + Q_CH);
-    Stage<DH, 8>::store(rqt, stage + 2 * Q_CH);
-    Stage<DH, 8>::store(rdot, stage + 2 * Q_CH + T_CH);
-    if (threadIdx.x < 128) reinterpret_cast<float*>(stage + 2 * Q_CH + 2 * T_CH)[threadIdx.x] = rstat;
-  };
-  Stage<64, CPRK>::load(rq, qsrc(t_first * 64));
-  Stage<64, CPRK>::load(rdo, dosrc(t_first * 64));
-  Stage<DH, 8>::load(rqt, qtsrc(t_first * 64));
-  Stage<DH, 8>::load(rdot, dotsrc(t_first * 64));
-  load_stat(t_first * 64);
-  store_all(lds);
-  __syncthreads();
+  issue_all(lds, t_first * 64);
+  stage_sync();
 
   for (int t = t_first; t < t_end; ++t) {
     const int it = t - t_first;
@@ -388,71 +389,68 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const bf16_t* __re
     const float* stat = reinterpret_cast<const float*>(qtile + 2 * Q_CH + 2 * T_CH);
     u32x4* nxt = lds + ((it + 1) & 1) * ST_CH;
     const int qq0 = t * 64, qqn = min(t + 1, t_end - 1) * 64;
-    Stage<64, CPRK>::load(rq, qsrc(qqn));
-    Stage<64, CPRK>::load(rdo, dosrc(qqn));
-    Stage<DH, 8>::load(rqt, qtsrc(qqn));
-    Stage<DH, 8>::load(rdot, dotsrc(qqn));
-    load_stat(qqn);
+    issue_all(nxt, qqn);
     __builtin_amdgcn_sched_barrier(0);
-    if (qq0 + 63 >= kw0) {          // wave-uniform: some query of the tile sees some key of this wave
-      const bool edge = (qq0 < kw0 + 31) || (qq0 + 63 >= S);          // causal boundary or padded queries inside the tile
-      // the 64 queries of the tile are processed as two groups of 32 to keep the score-shaped registers small
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
-        if (qq0 + 32 * mt + 31 < kw0) continue;          // wave-uniform: this group lies entirely above the diagonal
-        f32x16 sacc, dpacc, pacc;
-        zero16(sacc); zero16(dpacc);
+    for (int mt = 0; mt < 2; ++mt) {
+      const int qg0 = qq0 + 32 * mt;
+      if (qg0 + 31 < kw0) continue;          // wave-uniform: every query of the group lies above every key of this wave
+      f32x16 sacc, dpacc, pacc;
+      zero16(sacc); zero16(dpacc);
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-          sacc = MFMA(frag<CPRK>(qtile, mt * 32 + l32, 2 * s + lh), kf[s], sacc);
-          dpacc = MFMA(frag<CPRK>(dotile, mt * 32 + l32, 2 * s + lh), vf[s], dpacc);
+      for (int s = 0; s < KS; ++s) {
+        sacc = MFMA(frag<CPRK>(qtile, mt * 32 + l32, 2 * s + lh), kf[s], sacc);
+        dpacc = MFMA(frag<CPRK>(dotile, mt * 32 + l32, 2 * s + lh), vf[s], dpacc);
+      }
+      const bool edge = (qg0 < kw0 + 31) || (qg0 + 31 >= S);          // causal boundary or padded queries inside the group
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int rowb = mt * 32 + 8 * g + 4 * lh;          // 4 consecutive query rows of this lane
+        const float4 l4 = *reinterpret_cast<const float4*>(stat + rowb);
+        const float4 d4 = *reinterpret_cast<const float4*>(stat + 64 + rowb);
+        const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, ds[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int r = 4 * g + e;
+          float p = fast_exp2(fmaf(sacc[r], sc2, -ls[e] * LOG2E));
+          if (edge) { const int qq = qq0 + rowb + e; if (key > qq || qq >= S) p = 0.f; }
+          pacc[r] = p;
+          sacc[r] = p * (dpacc[r] - ds[e]);
         }
+      }
+      bf16x8 pf[2], dsf[2];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int rowb = mt * 32 + 8 * g + 4 * lh;          // 4 consecutive query rows of this lane
-          const float4 l4 = *reinterpret_cast<const float4*>(stat + rowb);
-          const float4 d4 = *reinterpret_cast<const float4*>(stat + 64 + rowb);
-          const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, ds[4] = {d4.x, d4.y, d4.z, d4.w};
+      for (int u = 0; u < 2; ++u) { pf[u] = pack8(pacc, 8 * u); dsf[u] = pack8(sacc, 8 * u); }
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int r = 4 * g + e;
-            float p = fast_exp2(sacc[r] * sc2 - ls[e]);
-            if (edge) { const int qq = qq0 + rowb + e; if (key > qq || qq >= S) p = 0.f; }
-            pacc[r] = p;
-            sacc[r] = p * (dpacc[r] - ds[e]);
-          }
+      for (int cc = 0; cc < CTH; ++cc) {
+        const int c = chalf * CTH + cc;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          dvacc[cc] = MFMA(frag<8>(dottile, c * 32 + l32, 2 * (2 * mt + u) + lh), pf[u], dvacc[cc]);
+          dkacc[cc] = MFMA(frag<8>(qttile, c * 32 + l32, 2 * (2 * mt + u) + lh), dsf[u], dkacc[cc]);
         }
-        bf16x8 pf[2], dsf[2];
-#pragma unroll
-        for (int u = 0; u < 2; ++u) { pf[u] = pack8(pacc, 8 * u); dsf[u] = pack8(sacc, 8 * u); }
-#pragma unroll
-        for (int c = 0; c < CT; ++c)
-#pragma unroll
-          for (int u = 0; u < 2; ++u) {
-            dvacc[c] = MFMA(frag<8>(dottile, c * 32 + l32, 2 * (2 * mt + u) + lh), pf[u], dvacc[c]);
-            dkacc[c] = MFMA(frag<8>(qttile, c * 32 + l32, 2 * (2 * mt + u) + lh), dsf[u], dkacc[c]);
-          }
       }
     }
     __builtin_amdgcn_sched_barrier(0);
-    store_all(nxt);
-    __syncthreads();
+    stage_sync();
   }
   if (key < S) {
     bf16_t* kp = dqkv + ((size_t)b * S + key) * ld + d + (size_t)head * DH + 4 * lh;
     bf16_t* vp = kp + d;
 #pragma unroll
-    for (int c = 0; c < CT; ++c)
+    for (int cc = 0; cc < CTH; ++cc) {
+      const int c = chalf * CTH + cc;
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         u32x2 wk, wv;
-        wk[0] = pack_bf16x2(dkacc[c][4 * g] * scale, dkacc[c][4 * g + 1] * scale);
-        wk[1] = pack_bf16x2(dkacc[c][4 * g + 2] * scale, dkacc[c][4 * g + 3] * scale);
-        wv[0] = pack_bf16x2(dvacc[c][4 * g], dvacc[c][4 * g + 1]);
-        wv[1] = pack_bf16x2(dvacc[c][4 * g + 2], dvacc[c][4 * g + 3]);
+        wk[0] = pack_bf16x2(dkacc[cc][4 * g] * scale, dkacc[cc][4 * g + 1] * scale);
+        wk[1] = pack_bf16x2(dkacc[cc][4 * g + 2] * scale, dkacc[cc][4 * g + 3] * scale);
+        wv[0] = pack_bf16x2(dvacc[cc][4 * g], dvacc[cc][4 * g + 1]);
+        wv[1] = pack_bf16x2(dvacc[cc][4 * g + 2], dvacc[cc][4 * g + 3]);
         *reinterpret_cast<u32x2*>(kp + c * 32 + 8 * g) = wk;
         *reinterpret_cast<u32x2*>(vp + c * 32 + 8 * g) = wv;
       }
+    }
   }
 }
 
@@ -486,9 +484,9 @@ static int bwd_launch(hipStream_t st, const void* qkv, const void* o, const floa
   head_transpose(st, qkv, 3 * d, d, at0, B, S, h, DH);          // AT(K)
   head_transpose(st, qkv, 3 * d, 0, at1, B, S, h, DH);          // AT(Q)
   head_transpose(st, dO, d, 0, at2, B, S, h, DH);               // AT(dO)
-  dim3 grid((S + 127) / 128, h, B);
-  attn_bwd_dq_kernel<DH><<<grid, 256, DQ_LDS, st>>>((const bf16_t*)qkv, (const bf16_t*)at0, (const bf16_t*)dO, lse, Dbuf, (bf16_t*)dqkv, S, Sp, h);
-  attn_bwd_dkv_kernel<DH><<<grid, 256, DKV_LDS, st>>>((const bf16_t*)qkv, (const bf16_t*)at1, (const bf16_t*)dO, (const bf16_t*)at2, lse, Dbuf,
+  dim3 grid((S + 127) / 128, h, B), grid_dq((S + 255) / 256, h, B);
+  attn_bwd_dq_kernel<DH><<<grid_dq, 512, DQ_LDS, st>>>((const bf16_t*)qkv, (const bf16_t*)at0, (const bf16_t*)dO, lse, Dbuf, (bf16_t*)dqkv, S, Sp, h);
+  attn_bwd_dkv_kernel<DH><<<grid, 512, DKV_LDS, st>>>((const bf16_t*)qkv, (const bf16_t*)at1, (const bf16_t*)dO, (const bf16_t*)at2, lse, Dbuf,
                                                       (bf16_t*)dqkv, S, Sp, h);
   return 0;
 }

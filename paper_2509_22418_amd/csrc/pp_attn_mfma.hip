@@ -45,19 +45,33 @@ __device__ __forceinline__ void zero16(f32x16& v) {
 // src: rows = positions (ld_src elements apart), head `head` at columns col0 + head*dh; dst: AT layout, row length Sp.
 __global__ void head_transpose_kernel(const bf16_t* __restrict__ src, int ld_src, int col0, bf16_t* __restrict__ dst,
                                       int S, int Sp, int h, int dh) {
-  __shared__ uint16_t tile[64][66];
+  __shared__ uint16_t tile[64][72];          // [position][column], rows 144 bytes apart (16-byte aligned)
   const int s0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
   const int bh = blockIdx.z, b = bh / h, head = bh % h;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  const bf16_t* sp = src + (size_t)b * S * ld_src + col0 + (size_t)head * dh;
-  for (int i = ty; i < 64; i += 4) {
-    const int s = s0 + i;
-    tile[i][tx] = (s < S) ? sp[(size_t)s * ld_src + c0 + tx].bits : (uint16_t)0;
+  const int t = threadIdx.x;
+  const uint16_t* sp = reinterpret_cast<const uint16_t*>(src) + (size_t)b * S * ld_src + col0 + (size_t)head * dh + c0;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {          // 16-byte loads: 8 columns of one position
+    const int r = (t >> 3) + 32 * i, c8 = (t & 7) * 8;
+    uint4 v = make_uint4(0, 0, 0, 0);          // positions beyond S are stored as zeros
+    if (s0 + r < S) v = *reinterpret_cast<const uint4*>(sp + (size_t)(s0 + r) * ld_src + c8);
+    *reinterpret_cast<uint4*>(&tile[r][c8]) = v;
   }
   __syncthreads();
-  const int sperm = (tx & ~12) | ((tx & 4) << 1) | ((tx & 8) >> 1);          // destination slot tx holds source position sperm
   uint16_t* dp = reinterpret_cast<uint16_t*>(dst) + ((size_t)bh * dh + c0) * Sp + s0;
-  for (int i = ty; i < 64; i += 4) dp[(size_t)i * Sp + tx] = tile[sperm][i];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {          // 16-byte stores: 8 destination slots of one column
+    const int c = (t >> 3) + 32 * i, p8 = (t & 7) * 8;
+    uint32_t w[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      // destination slot p holds source position perm(p) (bits 2 and 3 swapped)
+      const int pa = p8 + 2 * k, pb = pa + 1;
+      const int sa = (pa & ~12) | ((pa & 4) << 1) | ((pa & 8) >> 1), sb = (pb & ~12) | ((pb & 4) << 1) | ((pb & 8) >> 1);
+      w[k] = (uint32_t)tile[sa][c] | ((uint32_t)tile[sb][c] << 16);
+    }
+    *reinterpret_cast<uint4*>(dp + (size_t)c * Sp + p8) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
 }
 static void head_transpose(hipStream_t st, const void* src, int ld_src, int col0, void* dst, int B, int S, int h, int dh) {
   const int Sp = (S + 63) / 64 * 64;

@@ -158,6 +158,35 @@ void k_rmsnorm_dgamma(hipStream_t st, int dtype, const void* dy, const void* x, 
 template <class T>
 __global__ void rope_kernel(T* qkv, const float* __restrict__ cosb, const float* __restrict__ sinb, int S, int h, int dh,
                             size_t total, float sgn) {
+  // one thread rotates 8 consecutive pairs (i .. i+7, i+half .. i+half+7) of one (token, q|k, head)
+  const int half = dh >> 1, per_head = half >> 3;
+  const int d = h * dh;
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;      // over T * 2 * h * per_head
+  if (idx >= total) return;
+  const int i = (int)(idx % per_head) * 8;
+  size_t r = idx / per_head;
+  const int head = (int)(r % h); r /= h;
+  const int which = (int)(r % 2);
+  const size_t t = r / 2;
+  const int pos = (int)(t % S);
+  T* p = qkv + t * (size_t)(3 * d) + (size_t)which * d + (size_t)head * dh + i;
+  float a[8], b[8], c[8], sn[8];
+  load8(p, a);
+  load8(p + half, b);
+  load8(cosb + (size_t)pos * half + i, c);
+  load8(sinb + (size_t)pos * half + i, sn);
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const float s = sgn * sn[k], x = a[k], y = b[k];
+    a[k] = x * c[k] - y * s;
+    b[k] = x * s + y * c[k];
+  }
+  store8(p, a);
+  store8(p + half, b);
+}
+template <class T>
+__global__ void rope_scalar_kernel(T* qkv, const float* __restrict__ cosb, const float* __restrict__ sinb, int S, int h, int dh,
+                                   size_t total, float sgn) {
   const int half = dh >> 1;
   const int d = h * dh;
   size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;      // over T * 2 * h * half
@@ -175,8 +204,14 @@ __global__ void rope_kernel(T* qkv, const float* __restrict__ cosb, const float*
   p[half] = from_f32<T>(a * s + b * c);
 }
 void k_rope(hipStream_t st, int dtype, void* qkv, const float* cosb, const float* sinb, int B, int S, int h, int dh, int inverse) {
-  size_t total = (size_t)B * S * 2 * h * (dh / 2);
-  PP_DISPATCH(dtype, rope_kernel<T><<<cdiv(total, 256), 256, 0, st>>>((T*)qkv, cosb, sinb, S, h, dh, total, inverse ? -1.f : 1.f));
+  const float sgn = inverse ? -1.f : 1.f;
+  if ((dh / 2) % 8 == 0) {
+    size_t total = (size_t)B * S * 2 * h * (dh / 16);
+    PP_DISPATCH(dtype, rope_kernel<T><<<cdiv(total, 256), 256, 0, st>>>((T*)qkv, cosb, sinb, S, h, dh, total, sgn));
+  } else {
+    size_t total = (size_t)B * S * 2 * h * (dh / 2);
+    PP_DISPATCH(dtype, rope_scalar_kernel<T><<<cdiv(total, 256), 256, 0, st>>>((T*)qkv, cosb, sinb, S, h, dh, total, sgn));
+  }
 }
 
 // ------------------------------------------------------------------------------------------ SwiGLU
@@ -314,9 +349,38 @@ __global__ void transpose_kernel(const T* __restrict__ src, int ld_src, T* __res
     if (r < rows && c < cols) dst[(size_t)c * ld_dst + r] = tile[tx][i];
   }
 }
+// 64 x 64 tile of 2-byte elements with 16-byte global loads and stores; the 8 x 8 sub-blocks are turned in LDS.
+// Needs rows % 8 == 0, cols % 8 == 0, leading dimensions % 8 == 0 and 16-byte aligned bases.
+__global__ void transpose16_kernel(const uint16_t* __restrict__ src, int ld_src, uint16_t* __restrict__ dst, int ld_dst, int rows, int cols) {
+  __shared__ uint16_t tile[64][72];          // row pitch 144 bytes: 16-byte aligned rows, column reads spread over banks
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int r = (t >> 3) + 32 * i, c8 = (t & 7) * 8;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (r0 + r < rows && c0 + c8 < cols) v = *reinterpret_cast<const uint4*>(src + (size_t)(r0 + r) * ld_src + c0 + c8);
+    *reinterpret_cast<uint4*>(&tile[r][c8]) = v;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int c = (t >> 3) + 32 * i, r8 = (t & 7) * 8;          // output row c0 + c, output columns r0 + r8 .. +7
+    if (c0 + c < cols && r0 + r8 < rows) {
+      uint32_t w[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) w[k] = (uint32_t)tile[r8 + 2 * k][c] | ((uint32_t)tile[r8 + 2 * k + 1][c] << 16);
+      *reinterpret_cast<uint4*>(dst + (size_t)(c0 + c) * ld_dst + r0 + r8) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+  }
+}
 void k_transpose(hipStream_t st, int dtype, const void* src, int ld_src, void* dst, int ld_dst, int rows, int cols) {
   if (rows == 0 || cols == 0) return;
   dim3 grid(cdiv(cols, 64), cdiv(rows, 64));
+  if (dtype == 1 && rows % 8 == 0 && cols % 8 == 0 && ld_src % 8 == 0 && ld_dst % 8 == 0 && (((uintptr_t)src | (uintptr_t)dst) & 15) == 0) {
+    transpose16_kernel<<<grid, 256, 0, st>>>((const uint16_t*)src, ld_src, (uint16_t*)dst, ld_dst, rows, cols);
+    return;
+  }
   PP_DISPATCH(dtype, transpose_kernel<T><<<grid, 256, 0, st>>>((const T*)src, ld_src, (T*)dst, ld_dst, rows, cols));
 }
 
@@ -473,12 +537,33 @@ void k_attn_fwd_plain(hipStream_t st, int dtype, const void* qkv, void* o, float
 
 template <class T>
 __global__ void attn_D_kernel(const T* __restrict__ o, const T* __restrict__ dO, float* __restrict__ Dbuf, int S, int h, int dh, size_t total) {
-  // one wave per (b, s, head)
+  // D[b, head, s] = sum_c o * dO: dh/8 lanes per (token, head), 8 consecutive elements each (dh % 8 == 0)
+  const int lpr = dh >> 3;                                  // lanes per row: 2 .. 32 (power of two for dh 16, 32, 64, 128, 256)
+  const size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t row = gid / lpr;                             // (token, head) index
+  const int part = (int)(gid % lpr);
+  float acc = 0.f;
+  if (row < total) {
+    float a[8], b[8];
+    load8(o + row * dh + part * 8, a);
+    load8(dO + row * dh + part * 8, b);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc += a[k] * b[k];
+  }
+  for (int off = lpr >> 1; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+  if (row < total && part == 0) {
+    const int head = (int)(row % h);
+    const size_t t = row / h, b_ = t / S, s_ = t % S;
+    Dbuf[(b_ * h + head) * S + s_] = acc;
+  }
+}
+template <class T>
+__global__ void attn_D_generic_kernel(const T* __restrict__ o, const T* __restrict__ dO, float* __restrict__ Dbuf, int S, int h, int dh, size_t total) {
   const size_t w = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (w >= total) return;
   const int head = (int)(w % h);
-  const size_t t = w / h;                 // b*S + s
+  const size_t t = w / h;
   const size_t off = t * (size_t)(h * dh) + (size_t)head * dh;
   float acc = 0.f;
   for (int c = lane; c < dh; c += 64) acc += to_f32(o[off + c]) * to_f32(dO[off + c]);
@@ -487,7 +572,13 @@ __global__ void attn_D_kernel(const T* __restrict__ o, const T* __restrict__ dO,
 }
 void k_attn_D(hipStream_t st, int dtype, const void* o, const void* dO, float* Dbuf, int B, int S, int h, int dh) {
   size_t total = (size_t)B * S * h;
-  PP_DISPATCH(dtype, attn_D_kernel<T><<<cdiv(total, 4), 256, 0, st>>>((const T*)o, (const T*)dO, Dbuf, S, h, dh, total));
+  const int lpr = dh / 8;
+  if (dh % 8 == 0 && (lpr & (lpr - 1)) == 0 && lpr <= 64) {
+    size_t threads = total * lpr;
+    PP_DISPATCH(dtype, attn_D_kernel<T><<<cdiv(threads, 256), 256, 0, st>>>((const T*)o, (const T*)dO, Dbuf, S, h, dh, total));
+  } else {
+    PP_DISPATCH(dtype, attn_D_generic_kernel<T><<<cdiv(total, 4), 256, 0, st>>>((const T*)o, (const T*)dO, Dbuf, S, h, dh, total));
+  }
 }
 
 template <class T>

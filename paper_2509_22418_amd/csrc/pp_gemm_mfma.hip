@@ -250,8 +250,9 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
 #pragma unroll
     for (int i = 2 * half; i < 2 * half + 2; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
-  };
+      for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][j], fa[buf][i], acc[i][j], 0, 0, 0);
+  };          // B-panel rows as the MFMA's row operand: the accumulator tile is C^T, so a lane owns runs of 4 consecutive
+              // columns of ONE output row (8-byte bf16 / 16-byte fp32 stores instead of 2-byte ones)
   readf(0, 0, 0);
   for (int kt = 0; kt < nk; ++kt) {
     const int cur = (kt & (DL_STAGES - 1)) * DL_STAGE_CHUNKS, nxt = ((kt + 1) & (DL_STAGES - 1)) * DL_STAGE_CHUNKS;
@@ -285,35 +286,103 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);              // drain the clamped tail loads before the LDS is released
 
-  const int col_base = n0 + wn * 64 + l32;
-  const int row_base = m0 + wm * 128 + 4 * lhi;
-  if constexpr (OUT_F32) {
-    float* C = reinterpret_cast<float*>(Cv) + (size_t)z * (size_t)M * (size_t)ldc;
+  // ---- epilogue: element r of accumulator (i, j) is output row m0 + wm*128 + i*32 + lane%32,
+  //      column n0 + wn*64 + j*32 + 8*(r/4) + 4*(lane/32) + r%4
+  if constexpr (!OUT_F32) {
+    if ((N & 7) == 0 && (ldc & 7) == 0) {          // uniform: coalesced path through LDS
+      // Each wave turns its 128 x 64 sub-tile around in a private 8 KB LDS patch, 64 rows at a time: 8-byte pieces
+      // (4 consecutive columns of one row) are written, 16-byte row chunks are read back so that 8 lanes cover one
+      // 128-byte row segment of C (and of the residual).  Chunk c of row r sits at c ^ ((r >> 1) & 7).
+      __builtin_amdgcn_s_waitcnt(0x0070);
+      __builtin_amdgcn_s_barrier();                  // every wave is done with the staged panels
+      bf16_t* C = reinterpret_cast<bf16_t*>(Cv);
+      if constexpr (EPI == EPI_STORE) {
+        char* wbase = reinterpret_cast<char*>(lds) + wave * 8192;          // 64 rows x 128 bytes (bf16)
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+        for (int hi = 0; hi < 2; ++hi) {
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int col = col_base + j * 32;
+          for (int ii = 0; ii < 2; ++ii) {
+            const int i = 2 * hi + ii, row = ii * 32 + l32, sw2 = (row >> 1) & 7;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
-          if (row < M && col < N) C[(size_t)row * ldc + col] = acc[i][j][r];
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+              for (int g = 0; g < 4; ++g) {
+                const int q = j * 8 + 2 * g + lhi;          // 8-byte piece index within the 128-byte row
+                uint2 w;
+                w.x = f32x2_to_bf16x2(acc[i][j][4 * g], acc[i][j][4 * g + 1]);
+                w.y = f32x2_to_bf16x2(acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+                *reinterpret_cast<uint2*>(wbase + row * 128 + (((q >> 1) ^ sw2) << 4) + (q & 1) * 8) = w;
+              }
+          }
+#pragma unroll
+          for (int it = 0; it < 8; ++it) {
+            const int row = 8 * it + (lane >> 3), c = lane & 7;
+            const uint4 v = *reinterpret_cast<const uint4*>(wbase + row * 128 + ((c ^ ((row >> 1) & 7)) << 4));
+            const int grow = m0 + wm * 128 + hi * 64 + row, gcol = n0 + wn * 64 + c * 8;
+            if (grow < M && gcol < N) *reinterpret_cast<uint4*>(C + (size_t)grow * ldc + gcol) = v;
+          }
+        }
+      } else {
+        // residual add: the sum is formed in fp32 and rounded once, so the patch holds floats (64 rows x 256 bytes,
+        // 16-byte piece p of row r at p ^ (r & 15)); 16 lanes then cover one 128-byte row segment of R and of C
+        char* wbase = reinterpret_cast<char*>(lds) + wave * 16384;
+#pragma unroll
+        for (int hi = 0; hi < 2; ++hi) {
+#pragma unroll
+          for (int ii = 0; ii < 2; ++ii) {
+            const int i = 2 * hi + ii, row = ii * 32 + l32;
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+              for (int g = 0; g < 4; ++g) {
+                const int q = j * 8 + 2 * g + lhi;          // 16-byte piece (4 floats) index within the 256-byte row
+                *reinterpret_cast<float4*>(wbase + row * 256 + ((q ^ (row & 15)) << 4)) =
+                    make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+              }
+          }
+#pragma unroll
+          for (int it = 0; it < 16; ++it) {
+            const int row = 4 * it + (lane >> 4), c = lane & 15;
+            const float4 v = *reinterpret_cast<const float4*>(wbase + row * 256 + ((c ^ (row & 15)) << 4));
+            const int grow = m0 + wm * 128 + hi * 64 + row, gcol = n0 + wn * 64 + c * 4;
+            if (grow < M && gcol < N) {
+              const size_t off = (size_t)grow * ldc + gcol;
+              const uint2 rr = *reinterpret_cast<const uint2*>(R + off);
+              uint2 w;
+              w.x = f32x2_to_bf16x2(v.x + __uint_as_float(rr.x << 16), v.y + __uint_as_float(rr.x & 0xffff0000u));
+              w.y = f32x2_to_bf16x2(v.z + __uint_as_float(rr.y << 16), v.w + __uint_as_float(rr.y & 0xffff0000u));
+              *reinterpret_cast<uint2*>(C + off) = w;
+            }
+          }
         }
       }
-  } else {
-    bf16_t* C = reinterpret_cast<bf16_t*>(Cv);
+      return;
+    }
+  }
+  const int row_base = m0 + wm * 128 + l32;
+  const int col_base = n0 + wn * 64 + 4 * lhi;
+  const bool n_vec_ok = (N % 4 == 0) && (ldc % 4 == 0);
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 4; ++i) {
+    const int row = row_base + i * 32;
+    if (row >= M) continue;
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int col = col_base + j * 32;
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
-          if (row < M && col < N) {
-            float v = acc[i][j][r];
-            if constexpr (EPI == EPI_ADD_RES) v += to_f32(R[(size_t)row * ldc + col]);
-            C[(size_t)row * ldc + col] = from_f32<bf16_t>(v);
+      for (int g = 0; g < 4; ++g) {
+        const int col = col_base + j * 32 + 8 * g;
+        if (col >= N) continue;
+        float v[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+        if constexpr (OUT_F32) {
+          float* C = reinterpret_cast<float*>(Cv) + (size_t)z * (size_t)M * (size_t)ldc + (size_t)row * ldc + col;
+          if (n_vec_ok) *reinterpret_cast<float4*>(C) = make_float4(v[0], v[1], v[2], v[3]);
+          else for (int e = 0; e < 4 && col + e < N; ++e) C[e] = v[e];
+        } else {
+          bf16_t* C = reinterpret_cast<bf16_t*>(Cv) + (size_t)row * ldc + col;
+          for (int e = 0; e < 4 && col + e < N; ++e) {
+            float x = v[e];
+            if constexpr (EPI == EPI_ADD_RES) x += to_f32(R[(size_t)row * ldc + col + e]);
+            C[e] = from_f32<bf16_t>(x);
           }
         }
       }
@@ -358,7 +427,7 @@ int k_gemm_nt_mfma(hipStream_t st, const void* A, int lda, const void* B, int ld
   if (M < 1 || N < 1 || splits < 1 || K % splits) return 1;
   const int Ksplit = K / splits;
   if (Ksplit < BK || Ksplit % BK || lda % 8 || ldb % 8) return 1;
-  if (((uintptr_t)A | (uintptr_t)B) & 15) return 1;
+  if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C | (uintptr_t)R | (uintptr_t)partial) & 15) return 1;          // 16-byte vector accesses
   if (splits > 1) {
     if (!out_f32 || !partial || epi != EPI_STORE) return 1;
     return launch<EPI_STORE, true>(st, A, lda, B, ldb, partial, N, M, N, Ksplit, nullptr, splits);

@@ -44,7 +44,7 @@ def closed_form_flops(cfg, B, S, rho):
     return fwd, bwd
 
 
-def run_leg(torch, pp, gen, cfg, weights, mask, batches, steps, warmup, time_gemm):
+def run_leg(torch, pp, gen, cfg, weights, mask, batches, steps, warmup, time_gemm, outer=False, seed=0):
     torch.cuda.synchronize()
     torch.cuda.empty_cache()
     torch.cuda.reset_peak_memory_stats()
@@ -70,14 +70,45 @@ def run_leg(torch, pp, gen, cfg, weights, mask, batches, steps, warmup, time_gem
     cnt = m.counters()
     mem = m.memory_report()
     peak_alloc = torch.cuda.max_memory_allocated()
+    outer_res = None
+    if outer:
+        outer_res = time_outer_step(torch, pp, gen, m, seed)
     m.close()
     del m
-    return dict(seconds=dt, loss=loss, gemm=gt, counters=cnt, memory=mem, peak_alloc=peak_alloc)
+    return dict(seconds=dt, loss=loss, gemm=gt, counters=cnt, memory=mem, peak_alloc=peak_alloc, outer=outer_res)
+
+
+def time_outer_step(torch, pp, gen, m, seed, iters=50):
+    """Config 5: the node's share of the outer step on the trainable subset of the model that just ran its local
+    steps (theta_l = its current bf16 weights): delta, add the on-device sum of 31 seeded N(0, 1e-4) deltas, divide by
+    the count, Nesterov update (lr 0.7, momentum 0.9).  HBM-bound: 24 algorithmic bytes per element."""
+    n = m.n_trainable
+    theta_g = torch.from_numpy(m.get_state("p")).to(m.dev)          # fp32 global parameters ~ the masters before drift
+    mom = torch.zeros(n, dtype=torch.float32, device=m.dev)
+    others = torch.empty(n, dtype=torch.float32, device=m.dev)
+    keys = [gen.stream_key(seed, gen.STREAM_DELTAS, j + 1) for j in range(31)]
+    pp.pp_synth_delta_sum(m.h, others.data_ptr(), n, keys, 1e-4)
+    opt = pp.PPOuter(0.7, 0.9, 1, 32.0)
+    for _ in range(3):
+        pp.pp_outer_delta(m.h, theta_g.data_ptr(), mom.data_ptr(), others.data_ptr(), opt, None)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        pp.pp_outer_delta(m.h, theta_g.data_ptr(), mom.data_ptr(), others.data_ptr(), opt, None)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / iters
+    gbps = 24.0 * n / (ms * 1e-3) / 1e9
+    return dict(elements=int(n), ms_per_call=round(ms, 4), algorithmic_bytes_per_elem=24, achieved_gbps=round(gbps, 1),
+                peak_gbps=PEAK_HBM_GBPS, frac=round(gbps / PEAK_HBM_GBPS, 4),
+                note="one call = outer_kernel (delta, normalise, Nesterov, restart of local copy incl. 4 B/elem master write) + "
+                     "shadow refresh of the updated blocks; timed with events on the model's stream")
 
 
 def cpu_baseline(gen, cfg, weights, seed):
     """The fp64 oracle, as it stands, on a bounded sample of the same workload: full width (d, heads, d_ff, vocab),
-    first 2 of the layers, one sequence of 512 tokens, 1/32 FFN slice; one forward + restricted backward + AdamW."""
+    first 8 of the layers, one full-length sequence, 1/32 FFN slice; one forward + restricted backward + AdamW."""
     import numpy as np
     from oracle import pp_oracle as O
     try:
@@ -85,7 +116,7 @@ def cpu_baseline(gen, cfg, weights, seed):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
-    L_s, B_s, S_s = 2, 1, 512
+    L_s, B_s, S_s = min(8, cfg["n_layers"]), 1, cfg["seq"]
     scfg = dict(cfg, n_layers=L_s)
     keep = {k: v for k, v in weights.items() if not k.startswith("layers.") or int(k.split(".")[1]) < L_s}
     mask = gen.ffn_slice_mask(scfg, 0, 32)
@@ -146,9 +177,11 @@ def main():
         if n_slices == 8:
             legs.pop(1)
     results = {}
+    outer_step = None
     for name, mask, rho in legs:
         t1 = time.perf_counter()
-        r = run_leg(torch, pp, gen, cfg, weights, mask, batches, args.steps, args.warmup, time_gemm=True)
+        r = run_leg(torch, pp, gen, cfg, weights, mask, batches, args.steps, args.warmup, time_gemm=True,
+                    outer=(name == legs[0][0]), seed=args.seed)
         fwd, bwd = closed_form_flops(cfg, B, S, rho)
         ms = r["seconds"] / args.steps * 1e3
         executed = r["counters"]["flops_fwd"] + r["counters"]["flops_bwd"]
@@ -161,6 +194,8 @@ def main():
             gemm_ms_per_step=round(r["gemm"]["ms"] / args.steps, 3), gemm_launches_per_step=r["gemm"]["launches"] // args.steps,
             n_trainable=r["counters"]["n_trainable"], adamw_bytes=r["counters"]["adamw_bytes"],
             hbm_bytes=r["memory"], peak_allocated_gb=round(r["peak_alloc"] / 2 ** 30, 3), final_loss=round(r["loss"], 5))
+        if r["outer"]:
+            outer_step = r["outer"]
         log(f"[bench] leg {name}: {results[name]['tokens_per_s']} tokens/s, {ms:.2f} ms/step, "
             f"{results[name]['step_tflops']} TFLOP/s on executed FLOPs, GEMM {results[name]['gemm_tflops']} TFLOP/s "
             f"({time.perf_counter() - t1:.1f} s incl. setup)")
@@ -188,7 +223,7 @@ def main():
                                "Zipf(1.1) tokens, N(0,0.02) weights",
                    "global_batch": B, "seq_len": S, "trainable_fraction_of_ffn": f"1/{n_slices}"},
         "step_mfma_frac": mr["step_mfma_frac"], "peak_hbm_gb": mr["peak_allocated_gb"],
-        "roofline": roofline, "cpu_baseline": cpu, "legs": results,
+        "roofline": roofline, "cpu_baseline": cpu, "outer_step": outer_step, "legs": results,
     }
     print(json.dumps(out))
 

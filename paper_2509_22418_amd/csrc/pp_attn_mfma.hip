@@ -335,24 +335,28 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dq_kernel(const bf16_t* __res
 }
 
 // ------------------------------------------------------------------------------------------ backward: dK, dV
-// grid (ceil(S/128), h, B), 512 threads = 8 waves (2 per SIMD): waves w and w+4 own keys k0 + 32(w&3) .. +31 (lane
-// column = key) and each accumulates one half of the head dimension of dK and dV, so that every accumulator fits
-// in VGPRs; both recompute the score tile.  Query tiles of 64 (two groups of 32) from the diagonal on:
-// S = Q K^T, dP = dO V^T, P = exp(S - lse), dS = P * (dP - D); dV^T += AT(dO) P, dK^T += AT(Q) dS.
+// grid (ceil(S/128), h, B), 512 threads = 8 waves.  Waves w and w+4 own the same 32 keys k0 + 32(w&3) .. +31 (lane
+// column = key) and split the WORK, not the data: wave w ("V-wave") forms S = Q K^T and P = exp(S - lse), hands P
+// (bf16, in MFMA operand order) to its partner through a small LDS mailbox and accumulates dV^T += AT(dO) P; wave
+// w+4 ("K-wave") forms dP = dO V^T, picks P up, forms dS = P * (dP - D) and accumulates dK^T += AT(Q) dS.
+// Nothing is computed twice, each wave carries one 32 x dh accumulator, and everything stays in VGPRs.
+// Query tiles of 64 (two groups of 32) run from the diagonal to the end of the sequence.
 template <int DH>
 __global__ __launch_bounds__(512, 2) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ qt_at,
                                                                const bf16_t* __restrict__ dO, const bf16_t* __restrict__ dot_at,
                                                                const float* __restrict__ lse, const float* __restrict__ Dbuf,
                                                                bf16_t* __restrict__ dqkv, int S, int Sp, int h) {
-  constexpr int KS = DH / 16, CT = DH / 32, CTH = CT / 2, CPRK = DH / 8, NW = 8;
+  constexpr int KS = DH / 16, CT = DH / 32, CPRK = DH / 8, NW = 8;
   extern __shared__ u32x4 lds[];
   constexpr int Q_CH = 64 * CPRK, T_CH = DH * 8, ST_CH = 2 * Q_CH + 2 * T_CH + 32;          // + 64 lse and 64 D floats (32 chunks)
+  constexpr int MAIL0 = 2 * ST_CH;          // mailbox: [group parity 2][key group 4][fragment 2][lane 64] chunks
   const int d = h * DH, ld = 3 * d;
   const int kblk = blockIdx.x;          // earliest key blocks see the most queries: already first
   const int head = blockIdx.y, b = blockIdx.z;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), l32 = lane & 31, lh = lane >> 5;
-  const int chalf = wave >> 2;
-  const int k0 = kblk * 128, kw0 = k0 + (wave & 3) * 32;
+  const bool kwave = wave >= 4;          // false: V-wave (S, P, dV)   true: K-wave (dP, dS, dK)
+  const int kg = wave & 3;
+  const int k0 = kblk * 128, kw0 = k0 + kg * 32;
   const int key = kw0 + l32, keyc = min(key, S - 1);
   const bf16_t* base = qkv + (size_t)b * S * ld + (size_t)head * DH;
   const bf16_t* qtb = qt_at + ((size_t)(b * h + head) * DH) * Sp;
@@ -363,19 +367,15 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkv_kernel(const bf16_t* __re
   const int t_first = k0 / 64, t_end = (S + 63) / 64;
   const float scale = 1.0f / sqrtf((float)DH), sc2 = LOG2E * scale;
 
-  bf16x8 kf[KS], vf[KS];
+  bf16x8 cf[KS];          // this wave's column operand: K rows (V-wave) or V rows (K-wave) of its 32 keys
   {
-    const bf16_t* kp = base + (size_t)keyc * ld + d + 8 * lh;
-    const bf16_t* vp = base + (size_t)keyc * ld + 2 * d + 8 * lh;
+    const bf16_t* cp = base + (size_t)keyc * ld + (kwave ? 2 * d : d) + 8 * lh;
 #pragma unroll
-    for (int s = 0; s < KS; ++s) {
-      kf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(kp + 16 * s));
-      vf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(vp + 16 * s));
-    }
+    for (int s = 0; s < KS; ++s) cf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(cp + 16 * s));
   }
-  f32x16 dkacc[CTH], dvacc[CTH];
+  f32x16 oacc[CT];          // dV^T (V-wave) or dK^T (K-wave): rows = head-dim index, column = key
 #pragma unroll
-  for (int c = 0; c < CTH; ++c) { zero16(dkacc[c]); zero16(dvacc[c]); }
+  for (int c = 0; c < CT; ++c) zero16(oacc[c]);
 
   auto qsrc = [&](int qq0) { return [=](int row, int c) { return base + (size_t)min(qq0 + row, S - 1) * ld + c * 8; }; };
   auto dosrc = [&](int qq0) { return [=](int row, int c) { return dob + (size_t)min(qq0 + row, S - 1) * d + c * 8; }; };
@@ -396,11 +396,10 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkv_kernel(const bf16_t* __re
 
   for (int t = t_first; t < t_end; ++t) {
     const int it = t - t_first;
-    const u32x4* qtile = lds + (it & 1) * ST_CH;
-    const u32x4* dotile = qtile + Q_CH;
-    const u32x4* qttile = qtile + 2 * Q_CH;
-    const u32x4* dottile = qttile + T_CH;
-    const float* stat = reinterpret_cast<const float*>(qtile + 2 * Q_CH + 2 * T_CH);
+    const u32x4* stage = lds + (it & 1) * ST_CH;
+    const u32x4* rows_tile = stage + (kwave ? Q_CH : 0);                      // dO rows (K-wave) or Q rows (V-wave)
+    const u32x4* at_tile = stage + 2 * Q_CH + (kwave ? 0 : T_CH);            // AT(Q) (K-wave) or AT(dO) (V-wave)
+    const float* stat = reinterpret_cast<const float*>(stage + 2 * Q_CH + 2 * T_CH) + (kwave ? 64 : 0);
     u32x4* nxt = lds + ((it + 1) & 1) * ST_CH;
     const int qq0 = t * 64, qqn = min(t + 1, t_end - 1) * 64;
     issue_all(nxt, qqn);
@@ -408,63 +407,76 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkv_kernel(const bf16_t* __re
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
       const int qg0 = qq0 + 32 * mt;
-      if (qg0 + 31 < kw0) continue;          // wave-uniform: every query of the group lies above every key of this wave
-      f32x16 sacc, dpacc, pacc;
-      zero16(sacc); zero16(dpacc);
+      const bool active = qg0 + 31 >= kw0;          // wave-uniform, identical for both partners: some query of the group sees some key
+      u32x4* mail = lds + MAIL0 + ((mt * 4 + kg) * 2) * 64 + lane;
+      f32x16 x;
+      bf16x8 opf[2];
+      if (active) {
+        zero16(x);
 #pragma unroll
-      for (int s = 0; s < KS; ++s) {
-        sacc = MFMA(frag<CPRK>(qtile, mt * 32 + l32, 2 * s + lh), kf[s], sacc);
-        dpacc = MFMA(frag<CPRK>(dotile, mt * 32 + l32, 2 * s + lh), vf[s], dpacc);
-      }
-      const bool edge = (qg0 < kw0 + 31) || (qg0 + 31 >= S);          // causal boundary or padded queries inside the group
+        for (int s = 0; s < KS; ++s) x = MFMA(frag<CPRK>(rows_tile, mt * 32 + l32, 2 * s + lh), cf[s], x);
+        if (!kwave) {          // P = exp(S - lse), zero outside the causal triangle and for padded queries
+          const bool edge = (qg0 < kw0 + 31) || (qg0 + 31 >= S);
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int rowb = mt * 32 + 8 * g + 4 * lh;          // 4 consecutive query rows of this lane
-        const float4 l4 = *reinterpret_cast<const float4*>(stat + rowb);
-        const float4 d4 = *reinterpret_cast<const float4*>(stat + 64 + rowb);
-        const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, ds[4] = {d4.x, d4.y, d4.z, d4.w};
+          for (int g = 0; g < 4; ++g) {
+            const int rowb = mt * 32 + 8 * g + 4 * lh;          // 4 consecutive query rows of this lane
+            const float4 l4 = *reinterpret_cast<const float4*>(stat + rowb);
+            const float ls[4] = {l4.x, l4.y, l4.z, l4.w};
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int r = 4 * g + e;
-          float p = fast_exp2(fmaf(sacc[r], sc2, -ls[e] * LOG2E));
-          if (edge) { const int qq = qq0 + rowb + e; if (key > qq || qq >= S) p = 0.f; }
-          pacc[r] = p;
-          sacc[r] = p * (dpacc[r] - ds[e]);
+            for (int e = 0; e < 4; ++e) {
+              const int r = 4 * g + e;
+              float p = fast_exp2(fmaf(x[r], sc2, -ls[e] * LOG2E));
+              if (edge) { const int qq = qq0 + rowb + e; if (key > qq || qq >= S) p = 0.f; }
+              x[r] = p;
+            }
+          }
+          opf[0] = pack8(x, 0); opf[1] = pack8(x, 8);
+          mail[0] = __builtin_bit_cast(u32x4, opf[0]);
+          mail[64] = __builtin_bit_cast(u32x4, opf[1]);
         }
       }
-      bf16x8 pf[2], dsf[2];
+      __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0): the mailbox writes have landed
+      __builtin_amdgcn_s_barrier();
+      if (active) {
+        if (kwave) {          // dS = P * (dP - D)
+          const u32x4 p0 = mail[0], p1 = mail[64];
+          const uint32_t pw[8] = {p0[0], p0[1], p0[2], p0[3], p1[0], p1[1], p1[2], p1[3]};
 #pragma unroll
-      for (int u = 0; u < 2; ++u) { pf[u] = pack8(pacc, 8 * u); dsf[u] = pack8(sacc, 8 * u); }
+          for (int g = 0; g < 4; ++g) {
+            const int rowb = mt * 32 + 8 * g + 4 * lh;
+            const float4 d4 = *reinterpret_cast<const float4*>(stat + rowb);
+            const float ds[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
-      for (int cc = 0; cc < CTH; ++cc) {
-        const int c = chalf * CTH + cc;
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          dvacc[cc] = MFMA(frag<8>(dottile, c * 32 + l32, 2 * (2 * mt + u) + lh), pf[u], dvacc[cc]);
-          dkacc[cc] = MFMA(frag<8>(qttile, c * 32 + l32, 2 * (2 * mt + u) + lh), dsf[u], dkacc[cc]);
+            for (int e = 0; e < 4; ++e) {
+              const int r = 4 * g + e;
+              const uint32_t w = pw[r >> 1];
+              const float p = __uint_as_float((r & 1) ? (w & 0xffff0000u) : (w << 16));
+              x[r] = p * (x[r] - ds[e]);
+            }
+          }
+          opf[0] = pack8(x, 0); opf[1] = pack8(x, 8);
         }
+#pragma unroll
+        for (int c = 0; c < CT; ++c)
+#pragma unroll
+          for (int u = 0; u < 2; ++u) oacc[c] = MFMA(frag<8>(at_tile, c * 32 + l32, 2 * (2 * mt + u) + lh), opf[u], oacc[c]);
       }
     }
     __builtin_amdgcn_sched_barrier(0);
     stage_sync();
   }
   if (key < S) {
-    bf16_t* kp = dqkv + ((size_t)b * S + key) * ld + d + (size_t)head * DH + 4 * lh;
-    bf16_t* vp = kp + d;
+    const float osc = kwave ? scale : 1.0f;
+    bf16_t* op = dqkv + ((size_t)b * S + key) * ld + (kwave ? d : 2 * d) + (size_t)head * DH + 4 * lh;
 #pragma unroll
-    for (int cc = 0; cc < CTH; ++cc) {
-      const int c = chalf * CTH + cc;
+    for (int c = 0; c < CT; ++c)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        u32x2 wk, wv;
-        wk[0] = pack_bf16x2(dkacc[cc][4 * g] * scale, dkacc[cc][4 * g + 1] * scale);
-        wk[1] = pack_bf16x2(dkacc[cc][4 * g + 2] * scale, dkacc[cc][4 * g + 3] * scale);
-        wv[0] = pack_bf16x2(dvacc[cc][4 * g], dvacc[cc][4 * g + 1]);
-        wv[1] = pack_bf16x2(dvacc[cc][4 * g + 2], dvacc[cc][4 * g + 3]);
-        *reinterpret_cast<u32x2*>(kp + c * 32 + 8 * g) = wk;
-        *reinterpret_cast<u32x2*>(vp + c * 32 + 8 * g) = wv;
+        u32x2 w;
+        w[0] = pack_bf16x2(oacc[c][4 * g] * osc, oacc[c][4 * g + 1] * osc);
+        w[1] = pack_bf16x2(oacc[c][4 * g + 2] * osc, oacc[c][4 * g + 3] * osc);
+        *reinterpret_cast<u32x2*>(op + c * 32 + 8 * g) = w;
       }
-    }
   }
 }
 
@@ -490,7 +502,7 @@ template <int DH>
 static int bwd_launch(hipStream_t st, const void* qkv, const void* o, const float* lse, const void* dO, void* dqkv, float* Dbuf,
                       void* at0, void* at1, void* at2, int B, int S, int h) {
   constexpr int DQ_LDS = 2 * (2 * 64 * (DH / 8) + DH * 8) * 16;
-  constexpr int DKV_LDS = 2 * (2 * 64 * (DH / 8) + 2 * DH * 8 + 32) * 16;
+  constexpr int DKV_LDS = (2 * (2 * 64 * (DH / 8) + 2 * DH * 8 + 32) + 2 * 4 * 2 * 64) * 16;          // two stages + P mailbox
   static bool ok = set_lds(attn_bwd_dq_kernel<DH>, DQ_LDS) && set_lds(attn_bwd_dkv_kernel<DH>, DKV_LDS);
   if (!ok) return 1;
   const int Sp = (S + 63) / 64 * 64, d = h * DH;

@@ -1,0 +1,92 @@
+"""Boundary behaviour on the GPU: error codes, option handling, run-to-run reproducibility, mask re-arming."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import pp_inputs as gen
+import paper_2509_22418_amd as pp
+from paper_2509_22418_amd import binding as b
+from harness import HP, make_gpu_model
+
+pytestmark = pytest.mark.gpu
+
+SMALL = dict(n_layers=2, d_model=256, n_heads=2, d_ff=512, vocab=512, batch=2, seq=192, dtype="bf16")
+
+
+def test_error_codes_and_state_machine():
+    cfg = gen.make_config("tiny")
+    lib = pp.load_library()
+    m = pp.LocalStepModel(cfg, gen.ffn_slice_mask(cfg, 0, 4))
+    m.load_weights(gen.make_weights(cfg, 1))
+    tok, tgt = gen.make_tokens(cfg, 1)
+    td, gd = m.upload_tokens(tok, tgt)
+    opt = pp.PPAdamW(1e-3, 0.9, 0.95, 1e-8, 0.1)
+    # step before the mask is set
+    assert lib.pp_local_step(m.h, td.data_ptr(), gd.data_ptr(), 4, 32, ctypes.byref(opt), m.loss.data_ptr()) == -3
+    assert b"pp_set_trainable_mask" in lib.pp_last_error()
+    m.set_mask()
+    # shapes beyond the maxima, null pointers, bad hyper-parameters
+    assert lib.pp_local_step(m.h, td.data_ptr(), gd.data_ptr(), 5, 32, ctypes.byref(opt), m.loss.data_ptr()) == -1
+    assert lib.pp_local_step(m.h, td.data_ptr(), gd.data_ptr(), 4, 33, ctypes.byref(opt), m.loss.data_ptr()) == -1
+    assert lib.pp_local_step(m.h, None, gd.data_ptr(), 4, 32, ctypes.byref(opt), m.loss.data_ptr()) == -1
+    bad = pp.PPAdamW(1e-3, 1.5, 0.95, 1e-8, 0.1)
+    assert lib.pp_local_step(m.h, td.data_ptr(), gd.data_ptr(), 4, 32, ctypes.byref(bad), m.loss.data_ptr()) == -1
+    # tensor I/O: unknown names and wrong sizes
+    buf = np.zeros(10, dtype=np.float32)
+    assert lib.pp_get_tensor(m.h, b"layers.9.wq", buf.ctypes.data, buf.nbytes) == -1
+    assert lib.pp_get_tensor(m.h, b"embed", buf.ctypes.data, buf.nbytes) == -1
+    assert lib.pp_set_option(m.h, b"no_such_option", 1) == -1
+    # undersized state buffer for a bigger mask
+    big = b.make_mask(dict(all=1))
+    assert lib.pp_set_trainable_mask(m.h, ctypes.byref(big), m.state.data_ptr(), 256) == -1
+    # a valid step still works afterwards
+    loss = float(m.step(td, gd, HP).item())
+    assert np.isfinite(loss)
+    m.close()
+
+
+def test_step_is_bit_reproducible_and_mask_can_be_rearmed():
+    """Split-K partial sums, attention backward and the norm-gain reductions use fixed orders: two runs from the same
+    state give bit-identical gradients, losses and weights.  Setting the mask again restarts the optimizer state."""
+    cfg = gen.make_config("tiny", **SMALL)
+    weights = gen.make_weights(cfg, seed=31)
+    mask = gen.paper_mlp_mask(cfg, 1, 4)
+    tok, tgt = gen.make_tokens(cfg, seed=31)
+    runs = []
+    for rep in range(2):
+        m = make_gpu_model(cfg, weights, mask)
+        td, gd = m.upload_tokens(tok, tgt)
+        l1 = float(m.step(td, gd, HP).item())
+        g1 = m.get_state("g").copy()
+        l2 = float(m.step(td, gd, HP).item())
+        p2 = m.get_state("p").copy()
+        runs.append((l1, g1, l2, p2))
+        if rep == 1:
+            m.set_mask()          # re-arm: masters re-read from the current weights, m = v = 0, step counter 0
+            assert np.all(m.get_state("m") == 0) and np.all(m.get_state("v") == 0)
+            flat = m.get_state("p")
+            wq = m.get_weight("layers.0.wo", (cfg["d_model"], cfg["d_model"]))
+            assert np.isin(wq.reshape(-1)[:8], flat).all()
+        m.close()
+    assert runs[0][0] == runs[1][0] and runs[0][2] == runs[1][2]
+    assert np.array_equal(runs[0][1], runs[1][1])
+    assert np.array_equal(runs[0][3], runs[1][3])
+
+
+def test_plain_and_mfma_paths_agree():
+    cfg = gen.make_config("tiny", **SMALL)
+    weights = gen.make_weights(cfg, seed=32)
+    mask = gen.ffn_slice_mask(cfg, 0, 4)
+    tok, tgt = gen.make_tokens(cfg, seed=32)
+    out = []
+    for plain in (False, True):
+        m = make_gpu_model(cfg, weights, mask, force_plain=plain)
+        td, gd = m.upload_tokens(tok, tgt)
+        loss = float(m.step(td, gd, None).item())
+        out.append((loss, m.get_state("g").astype(np.float64)))
+        m.close()
+    assert abs(out[0][0] - out[1][0]) <= 2e-3 * abs(out[1][0])
+    a, bb = out[0][1], out[1][1]
+    assert float(a @ bb / (np.linalg.norm(a) * np.linalg.norm(bb))) >= 0.9999

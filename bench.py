@@ -148,6 +148,9 @@ def main():
     ap.add_argument("--legs", default="all", help="'main' = only the headline mask; 'all' = also rho=1/8 and all-trainable")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=1234)
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run three plain 1 GiB streaming copies (torch neg kernel, out = -in): under rocprofv3 --pmc FETCH_SIZE / "
+                         "WRITE_SIZE their readings give the counter scale for the HBM-traffic figures")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs one node's local step on ONE GPU (no collectives exist in it); "
@@ -162,6 +165,14 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
+    if args.calibrate:
+        # streaming kernel of known size: reads 1 GiB, writes 1 GiB (shows up as torch's neg kernel)
+        b = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        a = torch.empty_like(b)
+        for _ in range(3):
+            torch.neg(b, out=a)
+        torch.cuda.synchronize()
+        del a, b
     cfg = gen.make_config(args.workload)
     B, S = cfg["batch"], cfg["seq"]
     n_slices = cfg["n_slices"]

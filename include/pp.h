@@ -94,8 +94,11 @@ int pp_init_model(const pp_config* cfg, void* params_dev, size_t params_bytes, v
 
 /* Host <-> device copies of a named tensor (whole tensor, canonical layout, bytes must match exactly).
  * Besides the weight names, pp_get_tensor accepts "state.p", "state.m", "state.v", "state.g" (packed
- * fp32 subset, valid after pp_set_trainable_mask / a step) and "state.rows" (int64 canonical element
- * offset of every packed row of d_model elements).  Both block until the copy is done.
+ * fp32 subset, valid after pp_set_trainable_mask / a step), "state.rows" (int64 canonical element
+ * offset of every packed row of d_model elements), "shadow.<weight>" (the transposed read-only copy of wqkv, wo,
+ * wd or lm_head, shape [in x out]) and, for debugging, "dbg.<buffer>[.<layer>]" taps into the workspace
+ * (x, n1, qkv, o, xm, n2, gu, a, lse per layer; xL, logits, dx, dn, dqkv, dgu), sized for max_batch*max_seq tokens.
+ * Both block until the copy is done.
  * pp_set_tensor on a weight after pp_set_trainable_mask leaves the fp32 masters stale: set the mask again. */
 int pp_set_tensor(pp_model* m, const char* name, const void* host_src, size_t bytes);
 int pp_get_tensor(pp_model* m, const char* name, void* host_dst, size_t bytes);
@@ -136,7 +139,8 @@ int pp_get_counters(pp_model* m, double* flops_fwd, double* flops_bwd, double* a
 
 /* Options for tests and profiling.  "force_plain": 0 = automatic (MFMA kernels when shapes allow), 1 = force the
  * plain (non-MFMA) kernels.  "time_gemm": 1 = bracket every GEMM launch of later pp_local_step calls with a pair
- * of HIP events on the model's stream (host-side events only; no device memory), 0 = off; setting it resets the totals. */
+ * of HIP events on the model's stream (host-side events only; no device memory), 0 = off; setting it resets the totals.
+ * "gemm_variant" (process-wide; m may be NULL): 1 = direct-to-LDS MFMA GEMM (default), 0 = register-staged MFMA GEMM. */
 int pp_set_option(pp_model* m, const char* key, int64_t value);
 
 /* Blocks until the stream is idle, then returns the summed duration (ms), matmul FLOPs and number of the GEMM

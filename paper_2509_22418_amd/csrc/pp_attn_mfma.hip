@@ -118,6 +118,20 @@ __device__ __forceinline__ bf16x8 frag(const u32x4* tile, int row, int chunk) {
 
 constexpr float LOG2E = 1.4426950408889634f, LN2 = 0.6931471805599453f;
 
+// MFMA phases are written with the LDS fragment reads of step i+1 ahead of the MFMAs of step i (two fragment
+// buffers).  The compiler waits for ALL outstanding LDS reads whenever it needs one (it does not use partial
+// counts once LDS-DMA loads are in the kernel), so each step is written as: wait for the fragments already requested
+// (PP_STEP_BEGIN), request the next step's fragments, then issue this step's MFMAs -- the request then has the whole
+// MFMA group to land, instead of being waited for right after it was issued.
+#define PP_STEP_BEGIN()                         \
+  __builtin_amdgcn_sched_barrier(0);            \
+  __builtin_amdgcn_s_waitcnt(0xC07F);           \
+  __builtin_amdgcn_sched_barrier(0)
+#define PP_READS_THEN_MFMAS(R, M)                           \
+  __builtin_amdgcn_sched_group_barrier(0x100, R, 0);        \
+  __builtin_amdgcn_sched_group_barrier(0x008, M, 0);        \
+  __builtin_amdgcn_sched_barrier(0)
+
 // ------------------------------------------------------------------------------------------ forward
 // grid (ceil(S/128), h, B), 256 threads: wave w owns queries q0 + 32w .. +31; KV tiles of 64 keys.
 template <int DH>
@@ -165,10 +179,20 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
     if (kv0 <= qw0 + 31) {          // wave-uniform: some key of the tile is visible to some query of this wave
       f32x16 sacc[2];
       zero16(sacc[0]); zero16(sacc[1]);
+      {
+        bf16x8 kb[2][2];
+        kb[0][0] = frag<CPRK>(kt, l32, lh); kb[0][1] = frag<CPRK>(kt, 32 + l32, lh);
 #pragma unroll
-      for (int s = 0; s < KS; ++s) {
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt) sacc[mt] = MFMA(frag<CPRK>(kt, mt * 32 + l32, 2 * s + lh), qf[s], sacc[mt]);
+        for (int s = 0; s < KS; ++s) {
+          PP_STEP_BEGIN();
+          if (s + 1 < KS) {
+            kb[(s + 1) & 1][0] = frag<CPRK>(kt, l32, 2 * (s + 1) + lh);
+            kb[(s + 1) & 1][1] = frag<CPRK>(kt, 32 + l32, 2 * (s + 1) + lh);
+          }
+          sacc[0] = MFMA(kb[s & 1][0], qf[s], sacc[0]);
+          sacc[1] = MFMA(kb[s & 1][1], qf[s], sacc[1]);
+          PP_READS_THEN_MFMAS(2, 2);
+        }
       }
       float tmax = -INFINITY;          // row maximum of the raw scores (the scale is positive, so it commutes with max)
       if (kv0 + 63 > qw0) {          // wave-uniform: some (key, query) pair of the tile is masked
@@ -206,10 +230,26 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
       bf16x8 pf[4];
 #pragma unroll
       for (int t = 0; t < 4; ++t) pf[t] = pack8(sacc[t >> 1], 8 * (t & 1));
+      {          // steps run over (t, c) with c fastest: consecutive MFMAs hit different accumulators
+        __builtin_amdgcn_sched_barrier(0);
+        bf16x8 vb[2];
+        vb[0] = frag<8>(vtile, l32, lh);
+        vb[1] = frag<8>(vtile, (1 % CT) * 32 + l32, 2 * (1 / CT) + lh);
 #pragma unroll
-      for (int c = 0; c < CT; ++c)
-#pragma unroll
-        for (int t = 0; t < 4; ++t) oacc[c] = MFMA(frag<8>(vtile, c * 32 + l32, 2 * t + lh), pf[t], oacc[c]);
+        for (int sp = 0; sp < 2 * CT; ++sp) {          // two (t, c) steps per fence: 2 reads ahead, 2 MFMAs
+          PP_STEP_BEGIN();
+          bf16x8 cur0 = vb[0], cur1 = vb[1];
+          if (sp + 1 < 2 * CT) {
+            const int n0 = 2 * sp + 2, n1 = 2 * sp + 3;
+            vb[0] = frag<8>(vtile, (n0 % CT) * 32 + l32, 2 * (n0 / CT) + lh);
+            vb[1] = frag<8>(vtile, (n1 % CT) * 32 + l32, 2 * (n1 / CT) + lh);
+          }
+          const int a0 = 2 * sp, a1 = 2 * sp + 1;
+          oacc[a0 % CT] = MFMA(cur0, pf[a0 / CT], oacc[a0 % CT]);
+          oacc[a1 % CT] = MFMA(cur1, pf[a1 / CT], oacc[a1 % CT]);
+          PP_READS_THEN_MFMAS(2, 2);
+        }
+      }
     }
     __builtin_amdgcn_sched_barrier(0);
     stage_sync();
@@ -294,10 +334,21 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dq_kernel(const bf16_t* __res
       if (kg0 > qw0 + 31) continue;          // wave-uniform: every key of the group lies beyond every query of this wave
       f32x16 sacc, dpacc;
       zero16(sacc); zero16(dpacc);
+      {
+        __builtin_amdgcn_sched_barrier(0);
+        bf16x8 kb[2], vb[2];
+        kb[0] = frag<CPRK>(ktile, mt * 32 + l32, lh); vb[0] = frag<CPRK>(vtile, mt * 32 + l32, lh);
 #pragma unroll
-      for (int s = 0; s < KS; ++s) {
-        sacc = MFMA(frag<CPRK>(ktile, mt * 32 + l32, 2 * s + lh), qf[s], sacc);
-        dpacc = MFMA(frag<CPRK>(vtile, mt * 32 + l32, 2 * s + lh), dof[s], dpacc);
+        for (int s = 0; s < KS; ++s) {
+          PP_STEP_BEGIN();
+          if (s + 1 < KS) {
+            kb[(s + 1) & 1] = frag<CPRK>(ktile, mt * 32 + l32, 2 * (s + 1) + lh);
+            vb[(s + 1) & 1] = frag<CPRK>(vtile, mt * 32 + l32, 2 * (s + 1) + lh);
+          }
+          sacc = MFMA(kb[s & 1], qf[s], sacc);
+          dpacc = MFMA(vb[s & 1], dof[s], dpacc);
+          PP_READS_THEN_MFMAS(2, 2);
+        }
       }
       if (kg0 + 31 > qw0) {          // wave-uniform: the group straddles the diagonal
 #pragma unroll
@@ -312,10 +363,26 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dq_kernel(const bf16_t* __res
       }
       bf16x8 dsf[2];
       dsf[0] = pack8(sacc, 0); dsf[1] = pack8(sacc, 8);
+      {
+        __builtin_amdgcn_sched_barrier(0);
+        bf16x8 tb[2];
+        tb[0] = frag<8>(ttile, l32, 2 * (2 * mt) + lh);
+        tb[1] = frag<8>(ttile, (1 % CT) * 32 + l32, 2 * (2 * mt + 1 / CT) + lh);
 #pragma unroll
-      for (int c = 0; c < CT; ++c)
-#pragma unroll
-        for (int u = 0; u < 2; ++u) dqacc[c] = MFMA(frag<8>(ttile, c * 32 + l32, 2 * (2 * mt + u) + lh), dsf[u], dqacc[c]);
+        for (int sp = 0; sp < CT; ++sp) {          // two (u, c) steps per fence
+          PP_STEP_BEGIN();
+          bf16x8 cur0 = tb[0], cur1 = tb[1];
+          if (sp + 1 < CT) {
+            const int n0 = 2 * sp + 2, n1 = 2 * sp + 3;
+            tb[0] = frag<8>(ttile, (n0 % CT) * 32 + l32, 2 * (2 * mt + n0 / CT) + lh);
+            tb[1] = frag<8>(ttile, (n1 % CT) * 32 + l32, 2 * (2 * mt + n1 / CT) + lh);
+          }
+          const int a0 = 2 * sp, a1 = 2 * sp + 1;
+          dqacc[a0 % CT] = MFMA(cur0, dsf[a0 / CT], dqacc[a0 % CT]);
+          dqacc[a1 % CT] = MFMA(cur1, dsf[a1 / CT], dqacc[a1 % CT]);
+          PP_READS_THEN_MFMAS(2, 2);
+        }
+      }
     }
     __builtin_amdgcn_sched_barrier(0);
     stage_sync();
@@ -412,9 +479,26 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkv_kernel(const bf16_t* __re
       f32x16 x;
       bf16x8 opf[2];
       if (active) {
-        zero16(x);
+        {
+          __builtin_amdgcn_sched_barrier(0);
+          f32x16 x1;
+          zero16(x); zero16(x1);
+          bf16x8 rb[2][2];
+          rb[0][0] = frag<CPRK>(rows_tile, mt * 32 + l32, lh); rb[0][1] = frag<CPRK>(rows_tile, mt * 32 + l32, 2 + lh);
 #pragma unroll
-        for (int s = 0; s < KS; ++s) x = MFMA(frag<CPRK>(rows_tile, mt * 32 + l32, 2 * s + lh), cf[s], x);
+          for (int s2 = 0; s2 < KS / 2; ++s2) {          // two 16-deep slices per step, on two accumulators
+            PP_STEP_BEGIN();
+            if (s2 + 1 < KS / 2) {
+              rb[(s2 + 1) & 1][0] = frag<CPRK>(rows_tile, mt * 32 + l32, 2 * (2 * s2 + 2) + lh);
+              rb[(s2 + 1) & 1][1] = frag<CPRK>(rows_tile, mt * 32 + l32, 2 * (2 * s2 + 3) + lh);
+            }
+            x = MFMA(rb[s2 & 1][0], cf[2 * s2], x);
+            x1 = MFMA(rb[s2 & 1][1], cf[2 * s2 + 1], x1);
+            PP_READS_THEN_MFMAS(2, 2);
+          }
+#pragma unroll
+          for (int r = 0; r < 16; ++r) x[r] += x1[r];
+        }
         if (!kwave) {          // P = exp(S - lse), zero outside the causal triangle and for padded queries
           const bool edge = (qg0 < kw0 + 31) || (qg0 + 31 >= S);
 #pragma unroll
@@ -456,10 +540,26 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkv_kernel(const bf16_t* __re
           }
           opf[0] = pack8(x, 0); opf[1] = pack8(x, 8);
         }
+        {
+          __builtin_amdgcn_sched_barrier(0);
+          bf16x8 tb[2];
+          tb[0] = frag<8>(at_tile, l32, 2 * (2 * mt) + lh);
+          tb[1] = frag<8>(at_tile, (1 % CT) * 32 + l32, 2 * (2 * mt + 1 / CT) + lh);
 #pragma unroll
-        for (int c = 0; c < CT; ++c)
-#pragma unroll
-          for (int u = 0; u < 2; ++u) oacc[c] = MFMA(frag<8>(at_tile, c * 32 + l32, 2 * (2 * mt + u) + lh), opf[u], oacc[c]);
+          for (int sp = 0; sp < CT; ++sp) {          // two (u, c) steps per fence
+            PP_STEP_BEGIN();
+            bf16x8 cur0 = tb[0], cur1 = tb[1];
+            if (sp + 1 < CT) {
+              const int n0 = 2 * sp + 2, n1 = 2 * sp + 3;
+              tb[0] = frag<8>(at_tile, (n0 % CT) * 32 + l32, 2 * (2 * mt + n0 / CT) + lh);
+              tb[1] = frag<8>(at_tile, (n1 % CT) * 32 + l32, 2 * (2 * mt + n1 / CT) + lh);
+            }
+            const int a0 = 2 * sp, a1 = 2 * sp + 1;
+            oacc[a0 % CT] = MFMA(cur0, opf[a0 / CT], oacc[a0 % CT]);
+            oacc[a1 % CT] = MFMA(cur1, opf[a1 / CT], oacc[a1 % CT]);
+            PP_READS_THEN_MFMAS(2, 2);
+          }
+        }
       }
     }
     __builtin_amdgcn_sched_barrier(0);

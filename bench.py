@@ -214,7 +214,7 @@ def main():
     main_name = legs[0][0]
     mr = results[main_name]
     gemm_ms_launch = mr["gemm_ms_per_step"] / max(mr["gemm_launches_per_step"], 1)
-    roofline = dict(bound="mfma", kernel="gemm_nt_mfma_kernel (all forward / dX / dW GEMM launches of the step)",
+    roofline = dict(bound="mfma", kernel="gemm_nt_mfma_dl_kernel (all forward / dX / dW GEMM launches of the step)",
                     achieved=mr["gemm_tflops"], peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
                     frac=round(mr["gemm_tflops"] / PEAK_BF16_TFLOPS, 4) if mr["gemm_tflops"] else None, traffic=None,
                     avg_launch_ms=round(gemm_ms_launch, 4), launches_per_step=mr["gemm_launches_per_step"],

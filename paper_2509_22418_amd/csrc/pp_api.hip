@@ -149,7 +149,7 @@ struct pp_model {
   Mask mask{};
   std::vector<Seg> segs;
   int64_t n_train = 0;
-  int n_rows = 0, n_shadow_segs = 0, n_shadow_tiles = 0;
+  int n_rows = 0, n_shadow_segs = 0, n_shadow_tiles = 0, shadow_vec_ok = 0;
   float *sp = nullptr, *sm = nullptr, *sv = nullptr, *sg = nullptr;
   long step = 0;
   int force_plain = 0;
@@ -422,11 +422,12 @@ extern "C" int pp_set_trainable_mask(pp_model* m, const pp_mask* mask, void* sta
   // host tables: one RowInfo per packed row, one ShadowSeg per trainable block with a shadow image
   std::vector<RowInfo> rows;
   std::vector<ShadowSeg> ssegs;
-  int tiles = 0;
+  int tiles = 0, vec_ok = 1;
   for (const Seg& s : segs) {
     for (int i = 0; i < s.rows; ++i) rows.push_back(RowInfo{s.canon_off + (int64_t)i * d, s.decay ? 1.f : 0.f, 0});
     if (s.shadow_off >= 0) {
       ssegs.push_back(ShadowSeg{s.canon_off, s.shadow_off, s.rows, d, s.shadow_ld, tiles});
+      if ((s.rows | d | s.shadow_ld) & 7 || (s.canon_off | s.shadow_off) & 7) vec_ok = 0;
       tiles += ((s.rows + 63) / 64) * ((d + 63) / 64);
     }
   }
@@ -435,7 +436,7 @@ extern "C" int pp_set_trainable_mask(pp_model* m, const pp_mask* mask, void* sta
   if (!rows.empty()) HIPCHECK(hipMemcpy(m->wsp + plan.rows, rows.data(), rows.size() * sizeof(RowInfo), hipMemcpyHostToDevice));
   if (!ssegs.empty()) HIPCHECK(hipMemcpy(m->wsp + plan.segs, ssegs.data(), ssegs.size() * sizeof(ShadowSeg), hipMemcpyHostToDevice));
   m->ws = plan; m->mask = mk; m->segs = std::move(segs); m->n_train = n; m->n_rows = (int)rows.size();
-  m->n_shadow_segs = (int)ssegs.size(); m->n_shadow_tiles = tiles;
+  m->n_shadow_segs = (int)ssegs.size(); m->n_shadow_tiles = tiles; m->shadow_vec_ok = vec_ok;
   char* sb = (char*)state_dev;
   m->sp = (float*)sb; m->sm = (float*)(sb + quarter); m->sv = (float*)(sb + 2 * quarter); m->sg = (float*)(sb + 3 * quarter);
   k_pack_master(m->st, m->cfg.dtype, m->params, (const RowInfo*)(m->wsp + plan.rows), m->sp, m->n_rows, d);
@@ -637,7 +638,7 @@ extern "C" int pp_local_step(pp_model* m, const int32_t* tokens_dev, const int32
     const double bc1 = 1.0 - std::pow((double)opt->beta1, (double)m->step), bc2 = 1.0 - std::pow((double)opt->beta2, (double)m->step);
     k_adamw(st, dt, P, (const RowInfo*)(W + w.rows), m->sp, m->sm, m->sv, m->sg, m->n_rows, d, opt->lr, opt->beta1, opt->beta2,
             opt->eps, opt->weight_decay, (float)bc1, (float)bc2);
-    k_shadow_refresh(st, dt, P, shadow, (const ShadowSeg*)(W + w.segs), m->n_shadow_segs, m->n_shadow_tiles);
+    k_shadow_refresh(st, dt, P, shadow, (const ShadowSeg*)(W + w.segs), m->n_shadow_segs, m->n_shadow_tiles, m->shadow_vec_ok);
     m->adamw_bytes = (double)m->n_train * (28.0 + es);
   }
   hipError_t e = hipGetLastError();
@@ -654,7 +655,7 @@ extern "C" int pp_outer_delta(pp_model* m, float* theta_g_dev, float* momentum_d
   if (!(opt->lr >= 0.f) || !(opt->momentum >= 0.f)) return fail(PP_EINVAL, "pp_outer_delta: bad hyper-parameters");
   k_outer(m->st, m->cfg.dtype, m->params, (const RowInfo*)(m->wsp + m->ws.rows), m->sp, theta_g_dev, momentum_dev, others_sum_dev,
           delta_out_dev, m->n_rows, m->cfg.d_model, opt->lr, opt->momentum, opt->nesterov != 0, 1.0f / opt->m_count);
-  k_shadow_refresh(m->st, m->cfg.dtype, m->params, m->wsp + m->ws.shadow, (const ShadowSeg*)(m->wsp + m->ws.segs), m->n_shadow_segs, m->n_shadow_tiles);
+  k_shadow_refresh(m->st, m->cfg.dtype, m->params, m->wsp + m->ws.shadow, (const ShadowSeg*)(m->wsp + m->ws.segs), m->n_shadow_segs, m->n_shadow_tiles, m->shadow_vec_ok);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(PP_EHIP, std::string("pp_outer_delta: ") + hipGetErrorString(e));
   return PP_OK;

@@ -39,7 +39,7 @@ void k_count_valid(hipStream_t st, const int32_t* targets, int T, int V, int32_t
 int k_cross_entropy(hipStream_t st, int dtype, void* logits, const int32_t* targets, const int32_t* n_valid, float* rowloss, int T, int V);
 void k_loss_reduce(hipStream_t st, const float* rowloss, const int32_t* n_valid, float* loss, int T);
 void k_transpose(hipStream_t st, int dtype, const void* src, int ld_src, void* dst, int ld_dst, int rows, int cols);
-void k_shadow_refresh(hipStream_t st, int dtype, const void* params, void* shadow, const ShadowSeg* segs_dev, int n_segs, int n_tiles);
+void k_shadow_refresh(hipStream_t st, int dtype, const void* params, void* shadow, const ShadowSeg* segs_dev, int n_segs, int n_tiles, int vec_ok);
 
 // C[M x N] (ldc) = A[M x K] (lda) * B[N x K]^T (ldb)  [+ R[M x N] (ldc) if epi == EPI_ADD_RES]
 // out_f32: C is float regardless of dtype.  Plain (non-MFMA) kernel, any shape.

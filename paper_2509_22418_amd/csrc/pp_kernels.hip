@@ -411,8 +411,48 @@ __global__ void shadow_refresh_kernel(const T* __restrict__ params, T* __restric
     if (r < s.rows && c < s.cols) dst[(size_t)c * s.shadow_ld + r] = tile[tx][i];
   }
 }
-void k_shadow_refresh(hipStream_t st, int dtype, const void* params, void* shadow, const ShadowSeg* segs_dev, int n_segs, int n_tiles) {
+// 2-byte elements, 16-byte global accesses (block rows, columns, shadow leading dimension and offsets multiples of 8).
+__global__ void shadow_refresh16_kernel(const uint16_t* __restrict__ params, uint16_t* __restrict__ shadow, const ShadowSeg* __restrict__ segs, int n_segs) {
+  __shared__ uint16_t tile[64][72];
+  const int tileid = blockIdx.x;
+  int lo = 0, hi = n_segs - 1;
+  while (lo < hi) {
+    int mid = (lo + hi + 1) >> 1;
+    if (segs[mid].tile_start <= tileid) lo = mid; else hi = mid - 1;
+  }
+  const ShadowSeg s = segs[lo];
+  const int local = tileid - s.tile_start;
+  const int tiles_c = (s.cols + 63) / 64;
+  const int r0 = (local / tiles_c) * 64, c0 = (local % tiles_c) * 64;
+  const uint16_t* src = params + s.canon_off;
+  uint16_t* dst = shadow + s.shadow_off;
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int r = (t >> 3) + 32 * i, c8 = (t & 7) * 8;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (r0 + r < s.rows && c0 + c8 < s.cols) v = *reinterpret_cast<const uint4*>(src + (size_t)(r0 + r) * s.cols + c0 + c8);
+    *reinterpret_cast<uint4*>(&tile[r][c8]) = v;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int c = (t >> 3) + 32 * i, r8 = (t & 7) * 8;
+    if (c0 + c < s.cols && r0 + r8 < s.rows) {
+      uint32_t w[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) w[k] = (uint32_t)tile[r8 + 2 * k][c] | ((uint32_t)tile[r8 + 2 * k + 1][c] << 16);
+      *reinterpret_cast<uint4*>(dst + (size_t)(c0 + c) * s.shadow_ld + r0 + r8) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+  }
+}
+// vec_ok: every block has rows, cols, shadow_ld and both offsets multiples of 8 (checked by the caller on the host table)
+void k_shadow_refresh(hipStream_t st, int dtype, const void* params, void* shadow, const ShadowSeg* segs_dev, int n_segs, int n_tiles, int vec_ok) {
   if (n_segs == 0 || n_tiles == 0) return;
+  if (dtype == 1 && vec_ok) {
+    shadow_refresh16_kernel<<<n_tiles, 256, 0, st>>>((const uint16_t*)params, (uint16_t*)shadow, segs_dev, n_segs);
+    return;
+  }
   PP_DISPATCH(dtype, shadow_refresh_kernel<T><<<n_tiles, 256, 0, st>>>((const T*)params, (T*)shadow, segs_dev, n_segs));
 }
 

@@ -167,13 +167,19 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_kernel(const bf16_t* __restr
 // ------------------------------------------------------------------------------------------ direct-to-LDS variant
 // Same 256 x 256 tile and wave layout, but the panels go from global memory straight into LDS
 // (global_load_lds_dwordx4: lane l's 16 bytes land at M0 base + 16 l), no staging registers and no LDS write
-// instructions.  K advances in steps of 32 through FOUR 32 KB stages, so the loads of step kt+3 are issued while
-// step kt is multiplied.  LDS rows are 64 bytes = 4 chunks; a wave-load fills 16 consecutive rows; chunk c of row r
-// sits at chunk c ^ ((r >> 2) & 3) (the permutation is applied on the source side), which spreads the 16 rows of a
-// fragment read over all 64 banks.
-constexpr int DL_BK = 32, DL_STAGES = 4;
-constexpr int DL_STAGE_CHUNKS = (BM + BN) * 4;
-constexpr int DL_LDS_BYTES = DL_STAGES * DL_STAGE_CHUNKS * 16;
+// instructions.  The unit of transfer is 256 rows x 64 K-elements of ONE panel (32 KB): every row piece is a whole
+// 128-byte cache line, which matters because a compute unit can only keep a limited number of line requests in flight
+// -- half-line requests (a 32-deep K step of both panels) were measured to cap the kernel at about 2/3 of the speed
+// of this arrangement.  K advances in super-steps of 64 that consume one A unit and one B unit; five unit slots
+// (160 KB) form a ring, unit u = 2s (A of super-step s) or 2s+1 (B) living in slot u % 5.  During super-step s the B
+// unit of s+1 and then the A unit of s+2 are requested, so every unit has at least a whole super-step of matrix
+// work to arrive, and a single barrier per super-step both publishes the arrivals and frees the two consumed slots.  LDS rows are 128 bytes = 8 chunks; a wave-load fills 8 consecutive rows; chunk c of row r
+// sits at chunk c ^ ((r >> 1) & 7) (the permutation is applied on the source side), which spreads the 16 rows of a
+// fragment-read phase over all 64 banks.
+constexpr int DL_BK = 64, DL_SLOTS = 5;
+constexpr int DL_UNIT_CHUNKS = 256 * 8;
+constexpr int DL_LDS_BYTES = DL_SLOTS * DL_UNIT_CHUNKS * 16;
+static_assert(BM == 256 && BN == 256, "unit geometry assumes 256-row panels");
 #define PP_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define PP_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
 
@@ -199,31 +205,29 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
   const int z = blockIdx.y;
   const size_t kbase = (size_t)z * Ksplit;
 
-  // wave w fills row groups 2w and 2w+1 (16 rows each) of the A panel and of the B panel
-  const bf16_t* gsrc[4];
-  int ldst[4];          // chunk offset of the row group inside a stage (wave-uniform)
+  // wave w fills rows 32w .. 32w+31 of a unit with four loads of 8 rows (8 lanes per 128-byte row) each
+  const bf16_t* gA[4];
+  const bf16_t* gB[4];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int grp = wave * 2 + i;
-    const int row = grp * 16 + (lane >> 2);
-    const int c = (lane & 3) ^ ((row >> 2) & 3);
-    gsrc[i] = A + (size_t)min(m0 + row, M - 1) * lda + kbase + c * 8;
-    gsrc[2 + i] = B + (size_t)min(n0 + row, N - 1) * ldb + kbase + c * 8;
-    ldst[i] = grp * 64;
-    ldst[2 + i] = BM * 4 + grp * 64;
+  for (int i = 0; i < 4; ++i) {
+    const int row = wave * 32 + i * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ ((row >> 1) & 7);
+    gA[i] = A + (size_t)min(m0 + row, M - 1) * lda + kbase + c * 8;
+    gB[i] = B + (size_t)min(n0 + row, N - 1) * ldb + kbase + c * 8;
   }
-  const int nk = Ksplit / DL_BK;
-  auto issue = [&](int kt) {          // loads of K step kt (clamped) into stage kt % 4
-    const int ktc = min(kt, nk - 1);
-    u32x4* stage = lds + (kt & (DL_STAGES - 1)) * DL_STAGE_CHUNKS;
+  const int wdst = wave * 32 * 8;          // chunk offset of this wave's rows inside a unit (wave-uniform)
+  const int ns = Ksplit / DL_BK;
+  auto issue = [&](const bf16_t* const (&g)[4], int s, int slot) {          // unit of super-step s (clamped) into `slot`
+    const size_t koff = (size_t)min(s, ns - 1) * DL_BK;
+    u32x4* dst = lds + slot * DL_UNIT_CHUNKS + wdst;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      __builtin_amdgcn_global_load_lds(PP_GPTR(gsrc[i] + (size_t)ktc * DL_BK), PP_LPTR(stage + ldst[i]), 16, 0, 0);
+    for (int i = 0; i < 4; ++i) __builtin_amdgcn_global_load_lds(PP_GPTR(g[i] + koff), PP_LPTR(dst + i * 64), 16, 0, 0);
   };
-  issue(0); issue(1); issue(2);
+  auto m5 = [](int x) { return x >= DL_SLOTS ? x - DL_SLOTS : x; };
+  issue(gA, 0, 0); issue(gB, 0, 1); issue(gA, 1, 2);
   // Plain s_barrier (no fence): a workgroup fence would force vmcnt(0), i.e. wait for ALL loads in flight.  The only
   // LDS traffic here is DMA writes (tracked by vmcnt) and fragment reads (consumed by MFMAs before the barrier).
-  __builtin_amdgcn_s_waitcnt(0x0F70 | 8);          // vmcnt(8): step 0 has landed (steps 1, 2 may be in flight)
+  __builtin_amdgcn_s_waitcnt(0x0F70 | 4);          // vmcnt(4): both units of super-step 0 have landed
   __builtin_amdgcn_s_barrier();
 
   f32x16 acc[4][2];
@@ -234,56 +238,64 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int l32 = lane & 31, lhi = lane >> 5, sw = (l32 >> 2) & 3;
-  const int aRow = (wm * 128 + l32) * 4, bRow = BM * 4 + (wn * 64 + l32) * 4;
+  const int l32 = lane & 31, lhi = lane >> 5, sw = (l32 >> 1) & 7;
+  const int aRow = (wm * 128 + l32) * 8, bRow = (wn * 64 + l32) * 8;
   // Fragment registers are double-buffered: the reads of the next 16-deep slice are issued before the MFMAs of the
   // current one, so LDS latency hides behind matrix work inside one wavefront.
   bf16x8 fa[2][4], fb[2][2];
-  auto readf = [&](int buf, int stage_off, int s) {
-    const int pc = (2 * s + lhi) ^ sw;
+  auto readf = [&](int buf, int slot_a, int slot_b, int kk) {          // slice kk (0..3) of the units in the two slots
+    const int pc = (2 * kk + lhi) ^ sw;
+    const u32x4* pa = lds + slot_a * DL_UNIT_CHUNKS + aRow + pc;
+    const u32x4* pb = lds + slot_b * DL_UNIT_CHUNKS + bRow + pc;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) fa[buf][i] = __builtin_bit_cast(bf16x8, lds[stage_off + aRow + i * 32 * 4 + pc]);
+    for (int i = 0; i < 4; ++i) fa[buf][i] = __builtin_bit_cast(bf16x8, pa[i * 32 * 8]);
 #pragma unroll
-    for (int j = 0; j < 2; ++j) fb[buf][j] = __builtin_bit_cast(bf16x8, lds[stage_off + bRow + j * 32 * 4 + pc]);
+    for (int j = 0; j < 2; ++j) fb[buf][j] = __builtin_bit_cast(bf16x8, pb[j * 32 * 8]);
   };
-  auto mm = [&](int buf, int half) {          // 4 of the slice's 8 MFMAs
+  auto mm = [&](int buf) {          // the 8 MFMAs of one slice
 #pragma unroll
-    for (int i = 2 * half; i < 2 * half + 2; ++i)
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][j], fa[buf][i], acc[i][j], 0, 0, 0);
   };          // B-panel rows as the MFMA's row operand: the accumulator tile is C^T, so a lane owns runs of 4 consecutive
               // columns of ONE output row (8-byte bf16 / 16-byte fp32 stores instead of 2-byte ones)
-  readf(0, 0, 0);
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = (kt & (DL_STAGES - 1)) * DL_STAGE_CHUNKS, nxt = ((kt + 1) & (DL_STAGES - 1)) * DL_STAGE_CHUNKS;
-    issue(kt + 3);
+  // one fragment read is slotted behind each of the first six MFMAs of a slice (the in-order LDS counter then never
+  // makes this slice's MFMAs wait for the next slice's reads)
+#define PP_DL_INTERLEAVE(ID)                                    \
+  _Pragma("unroll") for (int g = 0; g < 6; ++g) {              \
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, ID);         \
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, ID);         \
+  }                                                             \
+  __builtin_amdgcn_sched_group_barrier(0x008, 2, ID);           \
+  __builtin_amdgcn_sched_barrier(0)
+
+  int sa = 0;          // slot of the A unit of the current super-step; its B unit is in the next slot of the ring
+  readf(0, 0, 1, 0);
+  for (int s = 0; s < ns; ++s) {
+    const int sb = m5(sa + 1), na = m5(sa + 2), nb2 = m5(sa + 3), fa2 = m5(sa + 4);
+    issue(gB, s + 1, nb2);          // slot of A(s-1): free since the barrier that ended super-step s-1
     __builtin_amdgcn_sched_barrier(0);
-    // slice 0 of step kt multiplies while slice 1 is read: one fragment read is slotted behind each of the first six
-    // MFMAs (the in-order LDS counter then never makes this slice's MFMAs wait for the next slice's reads)
-    readf(1, cur, 1);
-    mm(0, 0);
-    mm(0, 1);
-#pragma unroll
-    for (int g = 0; g < 6; ++g) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);          // 1 MFMA
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);          // 1 DS read
-    }
-    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+    readf(1, sa, sb, 1);
+    mm(0);
+    PP_DL_INTERLEAVE(0);
+    readf(0, sa, sb, 2);
+    mm(1);
+    PP_DL_INTERLEAVE(1);
+    issue(gA, s + 2, fa2);          // slot of B(s-1)
     __builtin_amdgcn_sched_barrier(0);
-    // vmcnt(8): step kt+1 has landed in this wave's row groups; lgkmcnt(0): this wave's reads of stage kt % 4 are done
-    __builtin_amdgcn_s_waitcnt(0x0070 | 8);
-    __builtin_amdgcn_s_barrier();                    // everybody's step kt+1 is in LDS; stage kt % 4 may be refilled
-    readf(0, nxt, 0);
-    mm(1, 0);
-    mm(1, 1);
-#pragma unroll
-    for (int g = 0; g < 6; ++g) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);
-    }
-    __builtin_amdgcn_sched_group_barrier(0x008, 2, 1);
-    __builtin_amdgcn_sched_barrier(0);
+    readf(1, sa, sb, 3);
+    mm(0);
+    PP_DL_INTERLEAVE(2);
+    // vmcnt(4): all but the newest unit, i.e. both units of super-step s+1, have landed in this wave's rows;
+    // lgkmcnt(0): this wave's reads of the current units are done
+    __builtin_amdgcn_s_waitcnt(0x0070 | 4);
+    __builtin_amdgcn_s_barrier();          // everybody's super-step s+1 is in LDS; the two current slots may be refilled
+    readf(0, na, nb2, 0);
+    mm(1);
+    PP_DL_INTERLEAVE(3);
+    sa = na;
   }
+#undef PP_DL_INTERLEAVE
   __builtin_amdgcn_s_waitcnt(0x0F70);              // drain the clamped tail loads before the LDS is released
 
   // ---- epilogue: element r of accumulator (i, j) is output row m0 + wm*128 + i*32 + lane%32,

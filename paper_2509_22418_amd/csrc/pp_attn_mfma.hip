@@ -105,6 +105,20 @@ struct Stage {
       __builtin_amdgcn_global_load_lds(PP_GPTR(src_of(row, c)), PP_LPTR(tile + w * 64), 16, 0, 0);
     }
   }
+  // same, with the source given as a wave-uniform base pointer plus a 32-bit byte offset per lane (off_of(row, chunk)):
+  // the address then needs one VGPR per load instead of a 64-bit pair, and no 64-bit vector arithmetic
+  template <class F>
+  static __device__ __forceinline__ void issue_u(u32x4* tile, int wave, int lane, const void* ubase, F&& off_of) {
+    constexpr int RPL = 64 / CPR;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const int w = wave * N + i;
+      const int row = w * RPL + lane / CPR;
+      const int c = (lane % CPR) ^ swz<CPR>(row);
+      const uint32_t off = off_of(row, c);
+      __builtin_amdgcn_global_load_lds(PP_GPTR(reinterpret_cast<const char*>(ubase) + off), PP_LPTR(tile + w * 64), 16, 0, 0);
+    }
+  }
 };
 // wait for this wave's DMA loads (vmcnt 0) and LDS reads (lgkmcnt 0), then meet the other waves
 __device__ __forceinline__ void stage_sync() {
@@ -117,6 +131,24 @@ __device__ __forceinline__ bf16x8 frag(const u32x4* tile, int row, int chunk) {
 }
 
 constexpr float LOG2E = 1.4426950408889634f, LN2 = 0.6931471805599453f;
+
+// Causal work is triangular: the blocks of one (batch, head) pair cost 1, 2, ..., n_blk tile passes.  The hardware
+// deals workgroups to the 8 XCDs round-robin by linear id, so an id -> (pair, block) map in which the cost has a
+// period of 8 or 16 ids gives some XCDs twice the work of others (measured: compute units busy 55-60 % of the kernel
+// time).  Here XCD k = id % 8 owns the pairs k, k+8, ... and walks them one after the other, heaviest block first:
+// every XCD gets the same work, and the blocks that run together on an XCD belong to a few pairs only, whose K/V (or
+// Q/dO) tiles they share in that XCD's L2.  Each workgroup takes block `rank` and its mirror image n-1-rank (constant cost), so the order of the ranks no longer
+// matters for balance.  1-D grid of n_pairs * n_blk workgroups, n_blk = number of such combined blocks per pair.
+__device__ __forceinline__ void causal_block_map(int id, int n_pairs, int n_blk, int& pair, int& rank) {
+  if ((n_pairs & 7) == 0) {
+    const int k = id & 7, j = id >> 3;
+    pair = (j / n_blk) * 8 + k;
+    rank = j % n_blk;
+  } else {          // fallback: equal-cost blocks at consecutive ids
+    pair = id % n_pairs;
+    rank = id / n_pairs;
+  }
+}
 
 // MFMA phases are written with the LDS fragment reads of step i+1 ahead of the MFMAs of step i (two fragment
 // buffers).  The compiler waits for ALL outstanding LDS reads whenever it needs one (it does not use partial
@@ -133,306 +165,319 @@ constexpr float LOG2E = 1.4426950408889634f, LN2 = 0.6931471805599453f;
   __builtin_amdgcn_sched_barrier(0)
 
 // ------------------------------------------------------------------------------------------ forward
-// grid (ceil(S/128), h, B), 256 threads: wave w owns queries q0 + 32w .. +31; KV tiles of 64 keys.
+// B*h*ceil(S/128) workgroups (see causal_block_map), 256 threads: wave w owns queries q0 + 32w .. +31; KV tiles of 64 keys.
 template <int DH>
 __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ vt,
-                                                           bf16_t* __restrict__ o, float* __restrict__ lse, int S, int Sp, int h) {
+                                                           bf16_t* __restrict__ o, float* __restrict__ lse, int S, int Sp, int h, int n_pairs, int n_blk) {
   constexpr int KS = DH / 16, CT = DH / 32, CPRK = DH / 8;
   extern __shared__ u32x4 lds[];
   constexpr int K_CH = 64 * CPRK, V_CH = DH * 8, ST_CH = K_CH + V_CH;
   const int d = h * DH, ld = 3 * d;
-  const int qblk = gridDim.x - 1 - blockIdx.x;          // heaviest (latest) query blocks first
-  const int head = blockIdx.y, b = blockIdx.z;
+  int pair, comb;
+  causal_block_map(blockIdx.x, n_pairs, (n_blk + 1) / 2, pair, comb);
+  const int head = pair % h, b = pair / h;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), l32 = lane & 31, lh = lane >> 5;
-  const int q0 = qblk * 128, qw0 = q0 + wave * 32;
-  const int q = qw0 + l32;
-  const bf16_t* base = qkv + (size_t)b * S * ld + (size_t)head * DH;
-  const bf16_t* vtb = vt + ((size_t)(b * h + head) * DH) * Sp;
-  const int n_tiles = min((q0 + 128 + 63) / 64, (S + 63) / 64);
+  // a late (heavy) query block, then its early (light) mirror image: every workgroup costs the same
+  for (int part = 0; part < 2; ++part) {
+    const int qblk = part == 0 ? n_blk - 1 - comb : comb;
+    if (part == 1 && qblk == n_blk - 1 - comb) break;
+    const int q0 = qblk * 128, qw0 = q0 + wave * 32;
+    const int q = qw0 + l32;
+    const bf16_t* base = qkv + (size_t)b * S * ld + (size_t)head * DH;
+    const bf16_t* vtb = vt + ((size_t)(b * h + head) * DH) * Sp;
+    const int n_tiles = min((q0 + 128 + 63) / 64, (S + 63) / 64);
 
-  bf16x8 qf[KS];
-  {
-    const bf16_t* qp = base + (size_t)min(q, S - 1) * ld + 8 * lh;
+    bf16x8 qf[KS];
+    {
+      const bf16_t* qp = base + (size_t)min(q, S - 1) * ld + 8 * lh;
 #pragma unroll
-    for (int s = 0; s < KS; ++s) qf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qp + 16 * s));
-  }
-  f32x16 oacc[CT];
-#pragma unroll
-  for (int c = 0; c < CT; ++c) zero16(oacc[c]);
-  float m_run = -INFINITY, l_run = 0.f;
-  const float sc2 = LOG2E / sqrtf((float)DH);
-
-  auto ksrc = [&](int kv0) { return [=](int row, int c) { return base + (size_t)min(kv0 + row, S - 1) * ld + d + c * 8; }; };
-  auto vsrc = [&](int kv0) { return [=](int row, int c) { return vtb + (size_t)row * Sp + kv0 + c * 8; }; };
-  Stage<64, CPRK>::issue(lds, wave, lane, ksrc(0));
-  Stage<DH, 8>::issue(lds + K_CH, wave, lane, vsrc(0));
-  stage_sync();
-
-  for (int j = 0; j < n_tiles; ++j) {
-    const u32x4* kt = lds + (j & 1) * ST_CH;
-    const u32x4* vtile = kt + K_CH;
-    u32x4* nxt = lds + ((j + 1) & 1) * ST_CH;
-    const int kv0 = j * 64, kvn = min(j + 1, n_tiles - 1) * 64;
-    Stage<64, CPRK>::issue(nxt, wave, lane, ksrc(kvn));
-    Stage<DH, 8>::issue(nxt + K_CH, wave, lane, vsrc(kvn));
-    __builtin_amdgcn_sched_barrier(0);
-    if (kv0 <= qw0 + 31) {          // wave-uniform: some key of the tile is visible to some query of this wave
-      f32x16 sacc[2];
-      zero16(sacc[0]); zero16(sacc[1]);
-      {
-        bf16x8 kb[2][2];
-        kb[0][0] = frag<CPRK>(kt, l32, lh); kb[0][1] = frag<CPRK>(kt, 32 + l32, lh);
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-          PP_STEP_BEGIN();
-          if (s + 1 < KS) {
-            kb[(s + 1) & 1][0] = frag<CPRK>(kt, l32, 2 * (s + 1) + lh);
-            kb[(s + 1) & 1][1] = frag<CPRK>(kt, 32 + l32, 2 * (s + 1) + lh);
-          }
-          sacc[0] = MFMA(kb[s & 1][0], qf[s], sacc[0]);
-          sacc[1] = MFMA(kb[s & 1][1], qf[s], sacc[1]);
-          PP_READS_THEN_MFMAS(2, 2);
-        }
-      }
-      float tmax = -INFINITY;          // row maximum of the raw scores (the scale is positive, so it commutes with max)
-      if (kv0 + 63 > qw0) {          // wave-uniform: some (key, query) pair of the tile is masked
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int key = kv0 + mt * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-            if (key > q) sacc[mt][r] = -INFINITY;
-            tmax = fmaxf(tmax, sacc[mt][r]);
-          }
-      } else {
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sacc[mt][r]);
-      }
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64)) * sc2;
-      const float m_new = fmaxf(m_run, tmax);
-      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;          // whole row masked so far (only for padded queries)
-      const float alpha = fast_exp2(m_run - m_use);
-      float psum = 0.f;
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { const float p = fast_exp2(fmaf(sacc[mt][r], sc2, -m_use)); sacc[mt][r] = p; psum += p; }
-      l_run = l_run * alpha + psum;
-      m_run = m_new;
-      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {          // wave-uniform: some row maximum moved
-#pragma unroll
-        for (int c = 0; c < CT; ++c)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) oacc[c][r] *= alpha;
-      }
-      bf16x8 pf[4];
-#pragma unroll
-      for (int t = 0; t < 4; ++t) pf[t] = pack8(sacc[t >> 1], 8 * (t & 1));
-      {          // steps run over (t, c) with c fastest: consecutive MFMAs hit different accumulators
-        __builtin_amdgcn_sched_barrier(0);
-        bf16x8 vb[2];
-        vb[0] = frag<8>(vtile, l32, lh);
-        vb[1] = frag<8>(vtile, (1 % CT) * 32 + l32, 2 * (1 / CT) + lh);
-#pragma unroll
-        for (int sp = 0; sp < 2 * CT; ++sp) {          // two (t, c) steps per fence: 2 reads ahead, 2 MFMAs
-          PP_STEP_BEGIN();
-          bf16x8 cur0 = vb[0], cur1 = vb[1];
-          if (sp + 1 < 2 * CT) {
-            const int n0 = 2 * sp + 2, n1 = 2 * sp + 3;
-            vb[0] = frag<8>(vtile, (n0 % CT) * 32 + l32, 2 * (n0 / CT) + lh);
-            vb[1] = frag<8>(vtile, (n1 % CT) * 32 + l32, 2 * (n1 / CT) + lh);
-          }
-          const int a0 = 2 * sp, a1 = 2 * sp + 1;
-          oacc[a0 % CT] = MFMA(cur0, pf[a0 / CT], oacc[a0 % CT]);
-          oacc[a1 % CT] = MFMA(cur1, pf[a1 / CT], oacc[a1 % CT]);
-          PP_READS_THEN_MFMAS(2, 2);
-        }
-      }
+      for (int s = 0; s < KS; ++s) qf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qp + 16 * s));
     }
-    __builtin_amdgcn_sched_barrier(0);
+    f32x16 oacc[CT];
+#pragma unroll
+    for (int c = 0; c < CT; ++c) zero16(oacc[c]);
+    float m_run = -INFINITY, l_run = 0.f;
+    const float sc2 = LOG2E / sqrtf((float)DH);
+
+    auto ksrc = [&](int kv0) { return [=](int row, int c) { return base + (size_t)min(kv0 + row, S - 1) * ld + d + c * 8; }; };
+    auto vsrc = [&](int kv0) { return [=](int row, int c) { return vtb + (size_t)row * Sp + kv0 + c * 8; }; };
+    Stage<64, CPRK>::issue(lds, wave, lane, ksrc(0));
+    Stage<DH, 8>::issue(lds + K_CH, wave, lane, vsrc(0));
     stage_sync();
-  }
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  if (q < S) {
-    const float inv = 1.0f / l_tot;
-    bf16_t* op = o + ((size_t)b * S + q) * d + (size_t)head * DH + 4 * lh;
+
+    for (int j = 0; j < n_tiles; ++j) {
+      const u32x4* kt = lds + (j & 1) * ST_CH;
+      const u32x4* vtile = kt + K_CH;
+      u32x4* nxt = lds + ((j + 1) & 1) * ST_CH;
+      const int kv0 = j * 64, kvn = min(j + 1, n_tiles - 1) * 64;
+      Stage<64, CPRK>::issue(nxt, wave, lane, ksrc(kvn));
+      Stage<DH, 8>::issue(nxt + K_CH, wave, lane, vsrc(kvn));
+      __builtin_amdgcn_sched_barrier(0);
+      if (kv0 <= qw0 + 31) {          // wave-uniform: some key of the tile is visible to some query of this wave
+        f32x16 sacc[2];
+        zero16(sacc[0]); zero16(sacc[1]);
+        {
+          bf16x8 kb[2][2];
+          kb[0][0] = frag<CPRK>(kt, l32, lh); kb[0][1] = frag<CPRK>(kt, 32 + l32, lh);
 #pragma unroll
-    for (int c = 0; c < CT; ++c)
+          for (int s = 0; s < KS; ++s) {
+            PP_STEP_BEGIN();
+            if (s + 1 < KS) {
+              kb[(s + 1) & 1][0] = frag<CPRK>(kt, l32, 2 * (s + 1) + lh);
+              kb[(s + 1) & 1][1] = frag<CPRK>(kt, 32 + l32, 2 * (s + 1) + lh);
+            }
+            sacc[0] = MFMA(kb[s & 1][0], qf[s], sacc[0]);
+            sacc[1] = MFMA(kb[s & 1][1], qf[s], sacc[1]);
+            PP_READS_THEN_MFMAS(2, 2);
+          }
+        }
+        float tmax = -INFINITY;          // row maximum of the raw scores (the scale is positive, so it commutes with max)
+        if (kv0 + 63 > qw0) {          // wave-uniform: some (key, query) pair of the tile is masked
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        u32x2 w;
-        w[0] = pack_bf16x2(oacc[c][4 * g] * inv, oacc[c][4 * g + 1] * inv);
-        w[1] = pack_bf16x2(oacc[c][4 * g + 2] * inv, oacc[c][4 * g + 3] * inv);
-        *reinterpret_cast<u32x2*>(op + c * 32 + 8 * g) = w;
+          for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int key = kv0 + mt * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+              if (key > q) sacc[mt][r] = -INFINITY;
+              tmax = fmaxf(tmax, sacc[mt][r]);
+            }
+        } else {
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sacc[mt][r]);
+        }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64)) * sc2;
+        const float m_new = fmaxf(m_run, tmax);
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;          // whole row masked so far (only for padded queries)
+        const float alpha = fast_exp2(m_run - m_use);
+        float psum = 0.f;
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) { const float p = fast_exp2(fmaf(sacc[mt][r], sc2, -m_use)); sacc[mt][r] = p; psum += p; }
+        l_run = l_run * alpha + psum;
+        m_run = m_new;
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {          // wave-uniform: some row maximum moved
+#pragma unroll
+          for (int c = 0; c < CT; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[c][r] *= alpha;
+        }
+        bf16x8 pf[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) pf[t] = pack8(sacc[t >> 1], 8 * (t & 1));
+        {          // steps run over (t, c) with c fastest: consecutive MFMAs hit different accumulators
+          __builtin_amdgcn_sched_barrier(0);
+          bf16x8 vb[2];
+          vb[0] = frag<8>(vtile, l32, lh);
+          vb[1] = frag<8>(vtile, (1 % CT) * 32 + l32, 2 * (1 / CT) + lh);
+#pragma unroll
+          for (int sp = 0; sp < 2 * CT; ++sp) {          // two (t, c) steps per fence: 2 reads ahead, 2 MFMAs
+            PP_STEP_BEGIN();
+            bf16x8 cur0 = vb[0], cur1 = vb[1];
+            if (sp + 1 < 2 * CT) {
+              const int n0 = 2 * sp + 2, n1 = 2 * sp + 3;
+              vb[0] = frag<8>(vtile, (n0 % CT) * 32 + l32, 2 * (n0 / CT) + lh);
+              vb[1] = frag<8>(vtile, (n1 % CT) * 32 + l32, 2 * (n1 / CT) + lh);
+            }
+            const int a0 = 2 * sp, a1 = 2 * sp + 1;
+            oacc[a0 % CT] = MFMA(cur0, pf[a0 / CT], oacc[a0 % CT]);
+            oacc[a1 % CT] = MFMA(cur1, pf[a1 / CT], oacc[a1 % CT]);
+            PP_READS_THEN_MFMAS(2, 2);
+          }
+        }
       }
-    if (lh == 0) lse[((size_t)b * h + head) * S + q] = (m_run + log2f(l_tot)) * LN2;
+      __builtin_amdgcn_sched_barrier(0);
+      stage_sync();
+    }
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    if (q < S) {
+      const float inv = 1.0f / l_tot;
+      bf16_t* op = o + ((size_t)b * S + q) * d + (size_t)head * DH + 4 * lh;
+#pragma unroll
+      for (int c = 0; c < CT; ++c)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          u32x2 w;
+          w[0] = pack_bf16x2(oacc[c][4 * g] * inv, oacc[c][4 * g + 1] * inv);
+          w[1] = pack_bf16x2(oacc[c][4 * g + 2] * inv, oacc[c][4 * g + 3] * inv);
+          *reinterpret_cast<u32x2*>(op + c * 32 + 8 * g) = w;
+        }
+      if (lh == 0) lse[((size_t)b * h + head) * S + q] = (m_run + log2f(l_tot)) * LN2;
+    }
   }
 }
 
 // ------------------------------------------------------------------------------------------ backward: dQ
-// grid (ceil(S/256), h, B), 512 threads = 8 waves (2 per SIMD, <= 256 registers each, so every MFMA keeps its
+// B*h*ceil(S/256) workgroups (see causal_block_map), 512 threads = 8 waves (2 per SIMD, <= 256 registers each, so every MFMA keeps its
 // accumulator in ordinary VGPRs): wave w owns queries q0 + 32w .. +31.  Per KV tile of 64 keys, in two groups of 32:
 // S^T = K Q^T, dP^T = V dO^T, dS^T = P^T * (dP^T - D), dQ^T += AT(K) dS^T.
 template <int DH>
 __global__ __launch_bounds__(512, 2) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ kt_at,
                                                               const bf16_t* __restrict__ dO, const float* __restrict__ lse,
-                                                              const float* __restrict__ Dbuf, bf16_t* __restrict__ dqkv, int S, int Sp, int h) {
+                                                              const float* __restrict__ Dbuf, bf16_t* __restrict__ dqkv, int S, int Sp, int h, int n_pairs, int n_blk) {
   constexpr int KS = DH / 16, CT = DH / 32, CPRK = DH / 8, NW = 8;
   extern __shared__ u32x4 lds[];
   constexpr int K_CH = 64 * CPRK, T_CH = DH * 8, ST_CH = 2 * K_CH + T_CH;
   const int d = h * DH, ld = 3 * d;
-  const int qblk = gridDim.x - 1 - blockIdx.x;
-  const int head = blockIdx.y, b = blockIdx.z;
+  int pair, comb;
+  causal_block_map(blockIdx.x, n_pairs, (n_blk + 1) / 2, pair, comb);
+  const int head = pair % h, b = pair / h;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), l32 = lane & 31, lh = lane >> 5;
-  const int q0 = qblk * 256, qw0 = q0 + wave * 32;
-  const int q = qw0 + l32, qc = min(q, S - 1);
-  const bf16_t* base = qkv + (size_t)b * S * ld + (size_t)head * DH;
-  const bf16_t* ktb = kt_at + ((size_t)(b * h + head) * DH) * Sp;
-  const int n_tiles = min((q0 + 256 + 63) / 64, (S + 63) / 64);
-  const float scale = 1.0f / sqrtf((float)DH), sc2 = LOG2E * scale;
+  // a late (heavy) query block, then its early (light) mirror image: every workgroup costs the same
+  for (int part = 0; part < 2; ++part) {
+    const int qblk = part == 0 ? n_blk - 1 - comb : comb;
+    if (part == 1 && qblk == n_blk - 1 - comb) break;
+    const int q0 = qblk * 256, qw0 = q0 + wave * 32;
+    const int q = qw0 + l32, qc = min(q, S - 1);
+    const bf16_t* base = qkv + (size_t)b * S * ld + (size_t)head * DH;
+    const bf16_t* ktb = kt_at + ((size_t)(b * h + head) * DH) * Sp;
+    const int n_tiles = min((q0 + 256 + 63) / 64, (S + 63) / 64);
+    const float scale = 1.0f / sqrtf((float)DH), sc2 = LOG2E * scale;
 
-  bf16x8 qf[KS], dof[KS];
-  {
-    const bf16_t* qp = base + (size_t)qc * ld + 8 * lh;
-    const bf16_t* dp = dO + ((size_t)b * S + qc) * d + (size_t)head * DH + 8 * lh;
+    bf16x8 qf[KS], dof[KS];
+    {
+      const bf16_t* qp = base + (size_t)qc * ld + 8 * lh;
+      const bf16_t* dp = dO + ((size_t)b * S + qc) * d + (size_t)head * DH + 8 * lh;
 #pragma unroll
-    for (int s = 0; s < KS; ++s) {
-      qf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qp + 16 * s));
-      dof[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(dp + 16 * s));
-    }
-  }
-  const size_t stat = ((size_t)b * h + head) * S + qc;
-  const float nlse2 = -lse[stat] * LOG2E, Dq = Dbuf[stat];
-  f32x16 dqacc[CT];
-#pragma unroll
-  for (int c = 0; c < CT; ++c) zero16(dqacc[c]);
-
-  auto ksrc = [&](int kv0) { return [=](int row, int c) { return base + (size_t)min(kv0 + row, S - 1) * ld + d + c * 8; }; };
-  auto vsrc = [&](int kv0) { return [=](int row, int c) { return base + (size_t)min(kv0 + row, S - 1) * ld + 2 * d + c * 8; }; };
-  auto tsrc = [&](int kv0) { return [=](int row, int c) { return ktb + (size_t)row * Sp + kv0 + c * 8; }; };
-  auto issue_all = [&](u32x4* stage, int kv0) {
-    Stage<64, CPRK, NW>::issue(stage, wave, lane, ksrc(kv0));
-    Stage<64, CPRK, NW>::issue(stage + K_CH, wave, lane, vsrc(kv0));
-    Stage<DH, 8, NW>::issue(stage + 2 * K_CH, wave, lane, tsrc(kv0));
-  };
-  issue_all(lds, 0);
-  stage_sync();
-
-  for (int j = 0; j < n_tiles; ++j) {
-    const u32x4* ktile = lds + (j & 1) * ST_CH;
-    const u32x4* vtile = ktile + K_CH;
-    const u32x4* ttile = ktile + 2 * K_CH;
-    u32x4* nxt = lds + ((j + 1) & 1) * ST_CH;
-    const int kv0 = j * 64, kvn = min(j + 1, n_tiles - 1) * 64;
-    issue_all(nxt, kvn);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
-      const int kg0 = kv0 + 32 * mt;
-      if (kg0 > qw0 + 31) continue;          // wave-uniform: every key of the group lies beyond every query of this wave
-      f32x16 sacc, dpacc;
-      zero16(sacc); zero16(dpacc);
-      {
-        __builtin_amdgcn_sched_barrier(0);
-        bf16x8 kb[2], vb[2];
-        kb[0] = frag<CPRK>(ktile, mt * 32 + l32, lh); vb[0] = frag<CPRK>(vtile, mt * 32 + l32, lh);
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-          PP_STEP_BEGIN();
-          if (s + 1 < KS) {
-            kb[(s + 1) & 1] = frag<CPRK>(ktile, mt * 32 + l32, 2 * (s + 1) + lh);
-            vb[(s + 1) & 1] = frag<CPRK>(vtile, mt * 32 + l32, 2 * (s + 1) + lh);
-          }
-          sacc = MFMA(kb[s & 1], qf[s], sacc);
-          dpacc = MFMA(vb[s & 1], dof[s], dpacc);
-          PP_READS_THEN_MFMAS(2, 2);
-        }
-      }
-      if (kg0 + 31 > qw0) {          // wave-uniform: the group straddles the diagonal
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = kg0 + 8 * (r >> 2) + 4 * lh + (r & 3);
-          const float p = key > q ? 0.f : fast_exp2(fmaf(sacc[r], sc2, nlse2));
-          sacc[r] = p * (dpacc[r] - Dq);
-        }
-      } else {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[r] = fast_exp2(fmaf(sacc[r], sc2, nlse2)) * (dpacc[r] - Dq);
-      }
-      bf16x8 dsf[2];
-      dsf[0] = pack8(sacc, 0); dsf[1] = pack8(sacc, 8);
-      {
-        __builtin_amdgcn_sched_barrier(0);
-        bf16x8 tb[2];
-        tb[0] = frag<8>(ttile, l32, 2 * (2 * mt) + lh);
-        tb[1] = frag<8>(ttile, (1 % CT) * 32 + l32, 2 * (2 * mt + 1 / CT) + lh);
-#pragma unroll
-        for (int sp = 0; sp < CT; ++sp) {          // two (u, c) steps per fence
-          PP_STEP_BEGIN();
-          bf16x8 cur0 = tb[0], cur1 = tb[1];
-          if (sp + 1 < CT) {
-            const int n0 = 2 * sp + 2, n1 = 2 * sp + 3;
-            tb[0] = frag<8>(ttile, (n0 % CT) * 32 + l32, 2 * (2 * mt + n0 / CT) + lh);
-            tb[1] = frag<8>(ttile, (n1 % CT) * 32 + l32, 2 * (2 * mt + n1 / CT) + lh);
-          }
-          const int a0 = 2 * sp, a1 = 2 * sp + 1;
-          dqacc[a0 % CT] = MFMA(cur0, dsf[a0 / CT], dqacc[a0 % CT]);
-          dqacc[a1 % CT] = MFMA(cur1, dsf[a1 / CT], dqacc[a1 % CT]);
-          PP_READS_THEN_MFMAS(2, 2);
-        }
+      for (int s = 0; s < KS; ++s) {
+        qf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qp + 16 * s));
+        dof[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(dp + 16 * s));
       }
     }
-    __builtin_amdgcn_sched_barrier(0);
+    const size_t stat = ((size_t)b * h + head) * S + qc;
+    const float nlse2 = -lse[stat] * LOG2E, Dq = Dbuf[stat];
+    f32x16 dqacc[CT];
+#pragma unroll
+    for (int c = 0; c < CT; ++c) zero16(dqacc[c]);
+
+    auto ksrc = [&](int kv0) { return [=](int row, int c) { return base + (size_t)min(kv0 + row, S - 1) * ld + d + c * 8; }; };
+    auto vsrc = [&](int kv0) { return [=](int row, int c) { return base + (size_t)min(kv0 + row, S - 1) * ld + 2 * d + c * 8; }; };
+    auto tsrc = [&](int kv0) { return [=](int row, int c) { return ktb + (size_t)row * Sp + kv0 + c * 8; }; };
+    auto issue_all = [&](u32x4* stage, int kv0) {
+      Stage<64, CPRK, NW>::issue(stage, wave, lane, ksrc(kv0));
+      Stage<64, CPRK, NW>::issue(stage + K_CH, wave, lane, vsrc(kv0));
+      Stage<DH, 8, NW>::issue(stage + 2 * K_CH, wave, lane, tsrc(kv0));
+    };
+    issue_all(lds, 0);
     stage_sync();
-  }
-  if (q < S) {
-    bf16_t* op = dqkv + ((size_t)b * S + q) * ld + (size_t)head * DH + 4 * lh;
+
+    for (int j = 0; j < n_tiles; ++j) {
+      const u32x4* ktile = lds + (j & 1) * ST_CH;
+      const u32x4* vtile = ktile + K_CH;
+      const u32x4* ttile = ktile + 2 * K_CH;
+      u32x4* nxt = lds + ((j + 1) & 1) * ST_CH;
+      const int kv0 = j * 64, kvn = min(j + 1, n_tiles - 1) * 64;
+      issue_all(nxt, kvn);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int c = 0; c < CT; ++c)
+      for (int mt = 0; mt < 2; ++mt) {
+        const int kg0 = kv0 + 32 * mt;
+        if (kg0 > qw0 + 31) continue;          // wave-uniform: every key of the group lies beyond every query of this wave
+        f32x16 sacc, dpacc;
+        zero16(sacc); zero16(dpacc);
+        {
+          __builtin_amdgcn_sched_barrier(0);
+          bf16x8 kb[2], vb[2];
+          kb[0] = frag<CPRK>(ktile, mt * 32 + l32, lh); vb[0] = frag<CPRK>(vtile, mt * 32 + l32, lh);
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        u32x2 w;
-        w[0] = pack_bf16x2(dqacc[c][4 * g] * scale, dqacc[c][4 * g + 1] * scale);
-        w[1] = pack_bf16x2(dqacc[c][4 * g + 2] * scale, dqacc[c][4 * g + 3] * scale);
-        *reinterpret_cast<u32x2*>(op + c * 32 + 8 * g) = w;
+          for (int s = 0; s < KS; ++s) {
+            PP_STEP_BEGIN();
+            if (s + 1 < KS) {
+              kb[(s + 1) & 1] = frag<CPRK>(ktile, mt * 32 + l32, 2 * (s + 1) + lh);
+              vb[(s + 1) & 1] = frag<CPRK>(vtile, mt * 32 + l32, 2 * (s + 1) + lh);
+            }
+            sacc = MFMA(kb[s & 1], qf[s], sacc);
+            dpacc = MFMA(vb[s & 1], dof[s], dpacc);
+            PP_READS_THEN_MFMAS(2, 2);
+          }
+        }
+        if (kg0 + 31 > qw0) {          // wave-uniform: the group straddles the diagonal
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = kg0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+            const float p = key > q ? 0.f : fast_exp2(fmaf(sacc[r], sc2, nlse2));
+            sacc[r] = p * (dpacc[r] - Dq);
+          }
+        } else {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sacc[r] = fast_exp2(fmaf(sacc[r], sc2, nlse2)) * (dpacc[r] - Dq);
+        }
+        bf16x8 dsf[2];
+        dsf[0] = pack8(sacc, 0); dsf[1] = pack8(sacc, 8);
+        {
+          __builtin_amdgcn_sched_barrier(0);
+          bf16x8 tb[2];
+          tb[0] = frag<8>(ttile, l32, 2 * (2 * mt) + lh);
+          tb[1] = frag<8>(ttile, (1 % CT) * 32 + l32, 2 * (2 * mt + 1 / CT) + lh);
+#pragma unroll
+          for (int sp = 0; sp < CT; ++sp) {          // two (u, c) steps per fence
+            PP_STEP_BEGIN();
+            bf16x8 cur0 = tb[0], cur1 = tb[1];
+            if (sp + 1 < CT) {
+              const int n0 = 2 * sp + 2, n1 = 2 * sp + 3;
+              tb[0] = frag<8>(ttile, (n0 % CT) * 32 + l32, 2 * (2 * mt + n0 / CT) + lh);
+              tb[1] = frag<8>(ttile, (n1 % CT) * 32 + l32, 2 * (2 * mt + n1 / CT) + lh);
+            }
+            const int a0 = 2 * sp, a1 = 2 * sp + 1;
+            dqacc[a0 % CT] = MFMA(cur0, dsf[a0 / CT], dqacc[a0 % CT]);
+            dqacc[a1 % CT] = MFMA(cur1, dsf[a1 / CT], dqacc[a1 % CT]);
+            PP_READS_THEN_MFMAS(2, 2);
+          }
+        }
       }
+      __builtin_amdgcn_sched_barrier(0);
+      stage_sync();
+    }
+    if (q < S) {
+      bf16_t* op = dqkv + ((size_t)b * S + q) * ld + (size_t)head * DH + 4 * lh;
+#pragma unroll
+      for (int c = 0; c < CT; ++c)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          u32x2 w;
+          w[0] = pack_bf16x2(dqacc[c][4 * g] * scale, dqacc[c][4 * g + 1] * scale);
+          w[1] = pack_bf16x2(dqacc[c][4 * g + 2] * scale, dqacc[c][4 * g + 3] * scale);
+          *reinterpret_cast<u32x2*>(op + c * 32 + 8 * g) = w;
+        }
+    }
   }
 }
 
 // ------------------------------------------------------------------------------------------ backward: dK, dV
-// grid (ceil(S/128), h, B), 512 threads = 8 waves.  Waves w and w+4 own the same 32 keys k0 + 32(w&3) .. +31 (lane
+// B*h*ceil(S/128) workgroups (see causal_block_map), 512 threads = 8 waves.  Waves w and w+4 own the same 32 keys k0 + 32(w&3) .. +31 (lane
 // column = key) and split the WORK, not the data: wave w ("V-wave") forms S = Q K^T and P = exp(S - lse), hands P
-// (bf16, in MFMA operand order) to its partner through a small LDS mailbox and accumulates dV^T += AT(dO) P; wave
+// (bf16, in MFMA operand order) to its partner through an LDS mailbox and accumulates dV^T += AT(dO) P; wave
 // w+4 ("K-wave") forms dP = dO V^T, picks P up, forms dS = P * (dP - D) and accumulates dK^T += AT(Q) dS.
 // Nothing is computed twice, each wave carries one 32 x dh accumulator, and everything stays in VGPRs.
-// Query tiles of 64 (two groups of 32) run from the diagonal to the end of the sequence.
-template <int DH>
-__global__ __launch_bounds__(512, 2) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ qt_at,
-                                                               const bf16_t* __restrict__ dO, const bf16_t* __restrict__ dot_at,
-                                                               const float* __restrict__ lse, const float* __restrict__ Dbuf,
-                                                               bf16_t* __restrict__ dqkv, int S, int Sp, int h) {
+// Query tiles of 64 run from the diagonal to the end of the sequence.  The K-waves run ONE TILE BEHIND the V-waves:
+// in iteration i the V-waves work on tile i (rows of Q, AT(dO)) and fill mailbox i % 2 while the K-waves work on tile
+// i-1 (rows of dO, AT(Q)) and empty mailbox (i-1) % 2, so the two waves that share a SIMD never wait for each other
+// inside an iteration -- one's exponentials overlap the other's matrix work -- and one barrier per tile is enough.
+// LDS: two "V sets" (Q rows + AT(dO)), two "K sets" (dO rows + AT(Q)), two mailboxes: 160 KB at dh = 128.
+// The per-query statistics (log-sum-exp for the V-waves, D for the K-waves) go straight from global memory into
+// registers, one tile ahead.
+template <int DH, bool kwave>          // kwave false: V-wave (S, P, dV)   true: K-wave (dP, dS, dK)
+__device__ __forceinline__ void attn_bwd_dkv_part(u32x4* lds, const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ qt_at,
+                                                  const bf16_t* __restrict__ dO, const bf16_t* __restrict__ dot_at,
+                                                  const float* __restrict__ lse, const float* __restrict__ Dbuf, bf16_t* __restrict__ dqkv,
+                                                  int S, int Sp, int h, int stats_vec, int head, int b, int kblk, int lane, int wave) {
   constexpr int KS = DH / 16, CT = DH / 32, CPRK = DH / 8, NW = 8;
-  extern __shared__ u32x4 lds[];
-  constexpr int Q_CH = 64 * CPRK, T_CH = DH * 8, ST_CH = 2 * Q_CH + 2 * T_CH + 32;          // + 64 lse and 64 D floats (32 chunks)
-  constexpr int MAIL0 = 2 * ST_CH;          // mailbox: [group parity 2][key group 4][fragment 2][lane 64] chunks
+  constexpr int R_CH = 64 * CPRK, T_CH = DH * 8, SET_CH = R_CH + T_CH;
+  constexpr int MAIL_CH = 2 * 4 * 2 * 64, MAIL0 = 4 * SET_CH;          // mailbox: [query group 2][key group 4][fragment 2][lane 64] chunks
   const int d = h * DH, ld = 3 * d;
-  const int kblk = blockIdx.x;          // earliest key blocks see the most queries: already first
-  const int head = blockIdx.y, b = blockIdx.z;
-  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), l32 = lane & 31, lh = lane >> 5;
-  const bool kwave = wave >= 4;          // false: V-wave (S, P, dV)   true: K-wave (dP, dS, dK)
-  const int kg = wave & 3;
+  const int l32 = lane & 31, lh = lane >> 5, kg = wave & 3;
   const int k0 = kblk * 128, kw0 = k0 + kg * 32;
   const int key = kw0 + l32, keyc = min(key, S - 1);
   const bf16_t* base = qkv + (size_t)b * S * ld + (size_t)head * DH;
   const bf16_t* qtb = qt_at + ((size_t)(b * h + head) * DH) * Sp;
   const bf16_t* dotb = dot_at + ((size_t)(b * h + head) * DH) * Sp;
   const bf16_t* dob = dO + (size_t)b * S * d + (size_t)head * DH;
-  const float* lseb = lse + ((size_t)b * h + head) * S;
-  const float* Db = Dbuf + ((size_t)b * h + head) * S;
-  const int t_first = k0 / 64, t_end = (S + 63) / 64;
+  const float* statb = (kwave ? Dbuf : lse) + ((size_t)b * h + head) * S;
+  const int t_first = k0 / 64, n_tiles = (S + 63) / 64 - t_first;
   const float scale = 1.0f / sqrtf((float)DH), sc2 = LOG2E * scale;
+  const float st_mul = kwave ? -1.0f : -sqrtf((float)DH);
 
   bf16x8 cf[KS];          // this wave's column operand: K rows (V-wave) or V rows (K-wave) of its 32 keys
   {
@@ -444,125 +489,142 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkv_kernel(const bf16_t* __re
 #pragma unroll
   for (int c = 0; c < CT; ++c) zero16(oacc[c]);
 
-  auto qsrc = [&](int qq0) { return [=](int row, int c) { return base + (size_t)min(qq0 + row, S - 1) * ld + c * 8; }; };
-  auto dosrc = [&](int qq0) { return [=](int row, int c) { return dob + (size_t)min(qq0 + row, S - 1) * d + c * 8; }; };
-  auto qtsrc = [&](int qq0) { return [=](int row, int c) { return qtb + (size_t)row * Sp + qq0 + c * 8; }; };
-  auto dotsrc = [&](int qq0) { return [=](int row, int c) { return dotb + (size_t)row * Sp + qq0 + c * 8; }; };
-  auto issue_all = [&](u32x4* stage, int qq0) {
-    Stage<64, CPRK, NW>::issue(stage, wave, lane, qsrc(qq0));
-    Stage<64, CPRK, NW>::issue(stage + Q_CH, wave, lane, dosrc(qq0));
-    Stage<DH, 8, NW>::issue(stage + 2 * Q_CH, wave, lane, qtsrc(qq0));
-    Stage<DH, 8, NW>::issue(stage + 2 * Q_CH + T_CH, wave, lane, dotsrc(qq0));
-    // per-row statistics: wave 0 brings the 64 log-sum-exps, wave 1 the 64 D values (4-byte pieces, lane l -> float l)
-    float* st = reinterpret_cast<float*>(stage + 2 * Q_CH + 2 * T_CH);
-    if (wave == 0) __builtin_amdgcn_global_load_lds(PP_GPTR(lseb + min(qq0 + lane, S - 1)), PP_LPTR(st), 4, 0, 0);
-    if (wave == 1) __builtin_amdgcn_global_load_lds(PP_GPTR(Db + min(qq0 + lane, S - 1)), PP_LPTR(st + 64), 4, 0, 0);
+  // sources as wave-uniform tile base + per-lane byte offset; rows past the end of the sequence repeat the last row
+  auto issue_v = [&](u32x4* set, int qq0) {
+    const int lim = S - 1 - qq0;
+    Stage<64, CPRK, NW>::issue_u(set, wave, lane, base + (size_t)qq0 * ld, [=](int row, int c) { return (uint32_t)(min(row, lim) * ld + c * 8) * 2u; });
+    Stage<DH, 8, NW>::issue_u(set + R_CH, wave, lane, dotb, [=](int row, int c) { return (uint32_t)(row * Sp + qq0 + c * 8) * 2u; });
   };
-  issue_all(lds, t_first * 64);
+  auto issue_k = [&](u32x4* set, int qq0) {
+    const int lim = S - 1 - qq0;
+    Stage<64, CPRK, NW>::issue_u(set, wave, lane, dob + (size_t)qq0 * d, [=](int row, int c) { return (uint32_t)(min(row, lim) * d + c * 8) * 2u; });
+    Stage<DH, 8, NW>::issue_u(set + R_CH, wave, lane, qtb, [=](int row, int c) { return (uint32_t)(row * Sp + qq0 + c * 8) * 2u; });
+  };
+  // statistics of this lane's 2 x 16 accumulator rows for the wave's next tile (rows past the end: any finite value)
+  float st[2][16];
+  auto load_stats = [&](int qq0) {
+    if (stats_vec && qq0 + 64 <= S) {          // wave-uniform
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const float4 v = *reinterpret_cast<const float4*>(statb + qq0 + mt * 32 + 8 * g + 4 * lh);
+          st[mt][4 * g] = v.x; st[mt][4 * g + 1] = v.y; st[mt][4 * g + 2] = v.z; st[mt][4 * g + 3] = v.w;
+        }
+    } else {          // ragged tail or unaligned rows: one base address, compile-time offsets, loads masked per lane
+      const float* sp = statb + qq0 + 4 * lh;
+      const int hi = S - (qq0 + 4 * lh);
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int o = mt * 32 + 8 * (r >> 2) + (r & 3);
+          st[mt][r] = o < hi ? sp[o] : 0.f;
+        }
+    }
+  };
+
+  issue_v(lds, t_first * 64);
+  load_stats(t_first * 64);          // first tile of either role
   stage_sync();
 
-  for (int t = t_first; t < t_end; ++t) {
-    const int it = t - t_first;
-    const u32x4* stage = lds + (it & 1) * ST_CH;
-    const u32x4* rows_tile = stage + (kwave ? Q_CH : 0);                      // dO rows (K-wave) or Q rows (V-wave)
-    const u32x4* at_tile = stage + 2 * Q_CH + (kwave ? 0 : T_CH);            // AT(Q) (K-wave) or AT(dO) (V-wave)
-    const float* stat = reinterpret_cast<const float*>(stage + 2 * Q_CH + 2 * T_CH) + (kwave ? 64 : 0);
-    u32x4* nxt = lds + ((it + 1) & 1) * ST_CH;
-    const int qq0 = t * 64, qqn = min(t + 1, t_end - 1) * 64;
-    issue_all(nxt, qqn);
+  for (int it = 0; it <= n_tiles; ++it) {
+    const int qv0 = (t_first + it) * 64;          // the V-waves' tile; the K-waves work on the one before it
+    if (it + 1 < n_tiles) issue_v(lds + ((it + 1) & 1) * SET_CH, qv0 + 64);          // last read in iteration it-1
+    if (it < n_tiles) issue_k(lds + (2 + (it & 1)) * SET_CH, qv0);                    // last read in iteration it-1
     __builtin_amdgcn_sched_barrier(0);
+    const int my_it = kwave ? it - 1 : it;          // index of the tile this wave works on now
+    const int qq0 = (t_first + my_it) * 64;
+    if (my_it >= 0 && my_it < n_tiles && qq0 + 63 >= kw0) {          // wave-uniform: some query of the tile sees some key of the wave
+      const u32x4* set = lds + ((kwave ? 2 : 0) + (my_it & 1)) * SET_CH;
+      const u32x4* rows_tile = set;                   // Q rows (V-wave) or dO rows (K-wave)
+      const u32x4* at_tile = set + R_CH;              // AT(dO) (V-wave) or AT(Q) (K-wave)
+      u32x4* mail = lds + MAIL0 + (my_it & 1) * MAIL_CH + (kg * 2) * 64 + lane;          // + mt * 512 + fragment * 64
+      // The accumulators start from the row statistics instead of zero, so the products come out as S - lse / scale
+      // (V-wave) or dP - D (K-wave) and the statistics need no registers while the tile is worked on.
+      f32x16 x[2];
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
-      const int qg0 = qq0 + 32 * mt;
-      const bool active = qg0 + 31 >= kw0;          // wave-uniform, identical for both partners: some query of the group sees some key
-      u32x4* mail = lds + MAIL0 + ((mt * 4 + kg) * 2) * 64 + lane;
-      f32x16 x;
-      bf16x8 opf[2];
-      if (active) {
-        {
-          __builtin_amdgcn_sched_barrier(0);
-          f32x16 x1;
-          zero16(x); zero16(x1);
-          bf16x8 rb[2][2];
-          rb[0][0] = frag<CPRK>(rows_tile, mt * 32 + l32, lh); rb[0][1] = frag<CPRK>(rows_tile, mt * 32 + l32, 2 + lh);
+      for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-          for (int s2 = 0; s2 < KS / 2; ++s2) {          // two 16-deep slices per step, on two accumulators
-            PP_STEP_BEGIN();
-            if (s2 + 1 < KS / 2) {
-              rb[(s2 + 1) & 1][0] = frag<CPRK>(rows_tile, mt * 32 + l32, 2 * (2 * s2 + 2) + lh);
-              rb[(s2 + 1) & 1][1] = frag<CPRK>(rows_tile, mt * 32 + l32, 2 * (2 * s2 + 3) + lh);
-            }
-            x = MFMA(rb[s2 & 1][0], cf[2 * s2], x);
-            x1 = MFMA(rb[s2 & 1][1], cf[2 * s2 + 1], x1);
-            PP_READS_THEN_MFMAS(2, 2);
+        for (int r = 0; r < 16; ++r) x[mt][r] = st[mt][r] * st_mul;
+      {          // both query groups at once: two independent accumulator chains
+        __builtin_amdgcn_sched_barrier(0);
+        bf16x8 rb[2][2];
+        rb[0][0] = frag<CPRK>(rows_tile, l32, lh); rb[0][1] = frag<CPRK>(rows_tile, 32 + l32, lh);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+          PP_STEP_BEGIN();
+          if (s + 1 < KS) {
+            rb[(s + 1) & 1][0] = frag<CPRK>(rows_tile, l32, 2 * (s + 1) + lh);
+            rb[(s + 1) & 1][1] = frag<CPRK>(rows_tile, 32 + l32, 2 * (s + 1) + lh);
           }
-#pragma unroll
-          for (int r = 0; r < 16; ++r) x[r] += x1[r];
-        }
-        if (!kwave) {          // P = exp(S - lse), zero outside the causal triangle and for padded queries
-          const bool edge = (qg0 < kw0 + 31) || (qg0 + 31 >= S);
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const int rowb = mt * 32 + 8 * g + 4 * lh;          // 4 consecutive query rows of this lane
-            const float4 l4 = *reinterpret_cast<const float4*>(stat + rowb);
-            const float ls[4] = {l4.x, l4.y, l4.z, l4.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const int r = 4 * g + e;
-              float p = fast_exp2(fmaf(x[r], sc2, -ls[e] * LOG2E));
-              if (edge) { const int qq = qq0 + rowb + e; if (key > qq || qq >= S) p = 0.f; }
-              x[r] = p;
-            }
-          }
-          opf[0] = pack8(x, 0); opf[1] = pack8(x, 8);
-          mail[0] = __builtin_bit_cast(u32x4, opf[0]);
-          mail[64] = __builtin_bit_cast(u32x4, opf[1]);
+          x[0] = MFMA(rb[s & 1][0], cf[s], x[0]);
+          x[1] = MFMA(rb[s & 1][1], cf[s], x[1]);
+          PP_READS_THEN_MFMAS(2, 2);
         }
       }
-      __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0): the mailbox writes have landed
-      __builtin_amdgcn_s_barrier();
-      if (active) {
-        if (kwave) {          // dS = P * (dP - D)
-          const u32x4 p0 = mail[0], p1 = mail[64];
-          const uint32_t pw[8] = {p0[0], p0[1], p0[2], p0[3], p1[0], p1[1], p1[2], p1[3]};
+      bf16x8 opf[4];
+      if (!kwave) {          // P = exp(S - lse), zero outside the causal triangle and for padded queries
+        if ((qq0 < kw0 + 31) || (qq0 + 63 >= S)) {          // wave-uniform: some pair of the tile is masked
+          // row offset o (compile-time) of this lane's element is masked iff o < lo (query before the key) or o >= hi (padding)
+          const int qb = qq0 + 4 * lh, lo = key - qb, hi = S - qb;
 #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const int rowb = mt * 32 + 8 * g + 4 * lh;
-            const float4 d4 = *reinterpret_cast<const float4*>(stat + rowb);
-            const float ds[4] = {d4.x, d4.y, d4.z, d4.w};
+          for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const int r = 4 * g + e;
-              const uint32_t w = pw[r >> 1];
-              const float p = __uint_as_float((r & 1) ? (w & 0xffff0000u) : (w << 16));
-              x[r] = p * (x[r] - ds[e]);
+            for (int r = 0; r < 16; ++r) {
+              const int o = mt * 32 + 8 * (r >> 2) + (r & 3);
+              const float p = fast_exp2(x[mt][r] * sc2);
+              x[mt][r] = (o < lo || o >= hi) ? 0.f : p;
             }
-          }
-          opf[0] = pack8(x, 0); opf[1] = pack8(x, 8);
+        } else {
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) x[mt][r] = fast_exp2(x[mt][r] * sc2);
         }
-        {
-          __builtin_amdgcn_sched_barrier(0);
-          bf16x8 tb[2];
-          tb[0] = frag<8>(at_tile, l32, 2 * (2 * mt) + lh);
-          tb[1] = frag<8>(at_tile, (1 % CT) * 32 + l32, 2 * (2 * mt + 1 / CT) + lh);
 #pragma unroll
-          for (int sp = 0; sp < CT; ++sp) {          // two (u, c) steps per fence
-            PP_STEP_BEGIN();
-            bf16x8 cur0 = tb[0], cur1 = tb[1];
-            if (sp + 1 < CT) {
-              const int n0 = 2 * sp + 2, n1 = 2 * sp + 3;
-              tb[0] = frag<8>(at_tile, (n0 % CT) * 32 + l32, 2 * (2 * mt + n0 / CT) + lh);
-              tb[1] = frag<8>(at_tile, (n1 % CT) * 32 + l32, 2 * (2 * mt + n1 / CT) + lh);
-            }
-            const int a0 = 2 * sp, a1 = 2 * sp + 1;
-            oacc[a0 % CT] = MFMA(cur0, opf[a0 / CT], oacc[a0 % CT]);
-            oacc[a1 % CT] = MFMA(cur1, opf[a1 / CT], oacc[a1 % CT]);
-            PP_READS_THEN_MFMAS(2, 2);
+        for (int u = 0; u < 4; ++u) {
+          opf[u] = pack8(x[u >> 1], 8 * (u & 1));
+          mail[(u >> 1) * 512 + (u & 1) * 64] = __builtin_bit_cast(u32x4, opf[u]);
+        }
+      } else {          // dS = P * (dP - D)
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const u32x4 pw = mail[(u >> 1) * 512 + (u & 1) * 64];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const int r = 8 * (u & 1) + e;
+            const uint32_t w = pw[e >> 1];
+            const float p = __uint_as_float((e & 1) ? (w & 0xffff0000u) : (w << 16));
+            x[u >> 1][r] *= p;
           }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) opf[u] = pack8(x[u >> 1], 8 * (u & 1));
+      }
+      {          // oacc[c] += AT tile rows c*32.., 16-query slice u  x  opf[u]; steps run over (u, c) with c fastest
+        __builtin_amdgcn_sched_barrier(0);
+        bf16x8 tb[2];
+        tb[0] = frag<8>(at_tile, l32, lh);
+        tb[1] = frag<8>(at_tile, (1 % CT) * 32 + l32, 2 * (1 / CT) + lh);
+#pragma unroll
+        for (int sp = 0; sp < 2 * CT; ++sp) {          // two (u, c) steps per fence
+          PP_STEP_BEGIN();
+          bf16x8 cur0 = tb[0], cur1 = tb[1];
+          if (sp + 1 < 2 * CT) {
+            const int n0 = 2 * sp + 2, n1 = 2 * sp + 3;
+            tb[0] = frag<8>(at_tile, (n0 % CT) * 32 + l32, 2 * (n0 / CT) + lh);
+            tb[1] = frag<8>(at_tile, (n1 % CT) * 32 + l32, 2 * (n1 / CT) + lh);
+          }
+          const int a0 = 2 * sp, a1 = 2 * sp + 1;
+          oacc[a0 % CT] = MFMA(cur0, opf[a0 / CT], oacc[a0 % CT]);
+          oacc[a1 % CT] = MFMA(cur1, opf[a1 / CT], oacc[a1 % CT]);
+          PP_READS_THEN_MFMAS(2, 2);
         }
       }
     }
     __builtin_amdgcn_sched_barrier(0);
+    if (my_it + 1 < n_tiles) load_stats(qq0 + 64);          // for this wave's next tile; lands before the barrier below
     stage_sync();
   }
   if (key < S) {
@@ -580,6 +642,27 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkv_kernel(const bf16_t* __re
   }
 }
 
+// The two roles are separate instantiations of the tile loop (their loop-invariant registers differ); both cross the
+// same number of barriers.
+template <int DH>
+__global__ __launch_bounds__(512, 2) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ qt_at,
+                                                               const bf16_t* __restrict__ dO, const bf16_t* __restrict__ dot_at,
+                                                               const float* __restrict__ lse, const float* __restrict__ Dbuf,
+                                                               bf16_t* __restrict__ dqkv, int S, int Sp, int h, int stats_vec, int n_pairs, int n_blk) {
+  extern __shared__ u32x4 lds[];
+  int pair, comb;
+  causal_block_map(blockIdx.x, n_pairs, (n_blk + 1) / 2, pair, comb);
+  const int head = pair % h, b = pair / h;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  // an early (heavy: it sees the most queries) key block, then its late (light) mirror image: every workgroup costs the same
+  for (int part = 0; part < 2; ++part) {
+    const int kblk = part == 0 ? comb : n_blk - 1 - comb;
+    if (part == 1 && kblk == comb) break;
+    if (wave >= 4) attn_bwd_dkv_part<DH, true>(lds, qkv, qt_at, dO, dot_at, lse, Dbuf, dqkv, S, Sp, h, stats_vec, head, b, kblk, lane, wave);
+    else attn_bwd_dkv_part<DH, false>(lds, qkv, qt_at, dO, dot_at, lse, Dbuf, dqkv, S, Sp, h, stats_vec, head, b, kblk, lane, wave);
+  }
+}
+
 // ------------------------------------------------------------------------------------------ host side
 template <class K>
 static bool set_lds(K kern, int bytes) {
@@ -594,15 +677,16 @@ static int fwd_launch(hipStream_t st, const void* qkv, void* o, float* lse, void
   if (!ok) return 1;
   const int Sp = (S + 63) / 64 * 64, d = h * DH;
   head_transpose(st, qkv, 3 * d, 2 * d, at0, B, S, h, DH);          // AT(V)
-  dim3 grid((S + 127) / 128, h, B);
-  attn_fwd_kernel<DH><<<grid, 256, 2 * (64 * (DH / 8) + DH * 8) * 16, st>>>((const bf16_t*)qkv, (const bf16_t*)at0, (bf16_t*)o, lse, S, Sp, h);
+  const int n_blk = (S + 127) / 128;
+  attn_fwd_kernel<DH><<<dim3(B * h * ((n_blk + 1) / 2)), 256, 2 * (64 * (DH / 8) + DH * 8) * 16, st>>>((const bf16_t*)qkv, (const bf16_t*)at0, (bf16_t*)o, lse, S, Sp, h,
+                                                                                           B * h, n_blk);
   return 0;
 }
 template <int DH>
 static int bwd_launch(hipStream_t st, const void* qkv, const void* o, const float* lse, const void* dO, void* dqkv, float* Dbuf,
                       void* at0, void* at1, void* at2, int B, int S, int h) {
   constexpr int DQ_LDS = 2 * (2 * 64 * (DH / 8) + DH * 8) * 16;
-  constexpr int DKV_LDS = (2 * (2 * 64 * (DH / 8) + 2 * DH * 8 + 32) + 2 * 4 * 2 * 64) * 16;          // two stages + P mailbox
+  constexpr int DKV_LDS = (4 * (64 * (DH / 8) + DH * 8) + 2 * (2 * 4 * 2 * 64)) * 16;          // two V sets, two K sets, two P mailboxes
   static bool ok = set_lds(attn_bwd_dq_kernel<DH>, DQ_LDS) && set_lds(attn_bwd_dkv_kernel<DH>, DKV_LDS);
   if (!ok) return 1;
   const int Sp = (S + 63) / 64 * 64, d = h * DH;
@@ -610,10 +694,12 @@ static int bwd_launch(hipStream_t st, const void* qkv, const void* o, const floa
   head_transpose(st, qkv, 3 * d, d, at0, B, S, h, DH);          // AT(K)
   head_transpose(st, qkv, 3 * d, 0, at1, B, S, h, DH);          // AT(Q)
   head_transpose(st, dO, d, 0, at2, B, S, h, DH);               // AT(dO)
-  dim3 grid((S + 127) / 128, h, B), grid_dq((S + 255) / 256, h, B);
-  attn_bwd_dq_kernel<DH><<<grid_dq, 512, DQ_LDS, st>>>((const bf16_t*)qkv, (const bf16_t*)at0, (const bf16_t*)dO, lse, Dbuf, (bf16_t*)dqkv, S, Sp, h);
-  attn_bwd_dkv_kernel<DH><<<grid, 512, DKV_LDS, st>>>((const bf16_t*)qkv, (const bf16_t*)at1, (const bf16_t*)dO, (const bf16_t*)at2, lse, Dbuf,
-                                                      (bf16_t*)dqkv, S, Sp, h);
+  const int nb_kv = (S + 127) / 128, nb_dq = (S + 255) / 256;
+  const int stats_vec = (S % 4 == 0) && ((reinterpret_cast<uintptr_t>(lse) | reinterpret_cast<uintptr_t>(Dbuf)) & 15) == 0;          // 16-byte loads of lse / D
+  attn_bwd_dq_kernel<DH><<<dim3(B * h * ((nb_dq + 1) / 2)), 512, DQ_LDS, st>>>((const bf16_t*)qkv, (const bf16_t*)at0, (const bf16_t*)dO, lse, Dbuf, (bf16_t*)dqkv, S, Sp, h,
+                                                                 B * h, nb_dq);
+  attn_bwd_dkv_kernel<DH><<<dim3(B * h * ((nb_kv + 1) / 2)), 512, DKV_LDS, st>>>((const bf16_t*)qkv, (const bf16_t*)at1, (const bf16_t*)dO, (const bf16_t*)at2, lse, Dbuf,
+                                                      (bf16_t*)dqkv, S, Sp, h, stats_vec, B * h, nb_kv);
   return 0;
 }
 

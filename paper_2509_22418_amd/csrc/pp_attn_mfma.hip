@@ -170,6 +170,7 @@ template <int DH>
 __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ vt,
                                                            bf16_t* __restrict__ o, float* __restrict__ lse, int S, int Sp, int h, int n_pairs, int n_blk) {
   constexpr int KS = DH / 16, CT = DH / 32, CPRK = DH / 8;
+  constexpr int CH = 4;          // fragment reads (= MFMAs) per fence; divides 2 KS and 4 CT
   extern __shared__ u32x4 lds[];
   constexpr int K_CH = 64 * CPRK, V_CH = DH * 8, ST_CH = K_CH + V_CH;
   const int d = h * DH, ld = 3 * d;
@@ -216,21 +217,33 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
       if (kv0 <= qw0 + 31) {          // wave-uniform: some key of the tile is visible to some query of this wave
         f32x16 sacc[2];
         zero16(sacc[0]); zero16(sacc[1]);
+        // MFMA steps n = 0 .. 2 KS - 1: key rows (n & 1) * 32.., head-dim slice n >> 1; CH steps per fence
+        auto fragK = [&](int n) { return frag<CPRK>(kt, (n & 1) * 32 + l32, 2 * (n >> 1) + lh); };
+        auto fragV = [&](int n) { return frag<8>(vtile, (n % CT) * 32 + l32, 2 * (n / CT) + lh); };
         {
-          bf16x8 kb[2][2];
-          kb[0][0] = frag<CPRK>(kt, l32, lh); kb[0][1] = frag<CPRK>(kt, 32 + l32, lh);
+          bf16x8 kb[2][CH];
 #pragma unroll
-          for (int s = 0; s < KS; ++s) {
+          for (int i = 0; i < CH; ++i) kb[0][i] = fragK(i);
+#pragma unroll
+          for (int c = 0; c < 2 * KS / CH; ++c) {
             PP_STEP_BEGIN();
-            if (s + 1 < KS) {
-              kb[(s + 1) & 1][0] = frag<CPRK>(kt, l32, 2 * (s + 1) + lh);
-              kb[(s + 1) & 1][1] = frag<CPRK>(kt, 32 + l32, 2 * (s + 1) + lh);
+            if (c + 1 < 2 * KS / CH) {
+#pragma unroll
+              for (int i = 0; i < CH; ++i) kb[(c + 1) & 1][i] = fragK((c + 1) * CH + i);
             }
-            sacc[0] = MFMA(kb[s & 1][0], qf[s], sacc[0]);
-            sacc[1] = MFMA(kb[s & 1][1], qf[s], sacc[1]);
-            PP_READS_THEN_MFMAS(2, 2);
+#pragma unroll
+            for (int i = 0; i < CH; ++i) {
+              const int n = c * CH + i;
+              sacc[n & 1] = MFMA(kb[c & 1][i], qf[n >> 1], sacc[n & 1]);
+            }
+            PP_READS_THEN_MFMAS(CH, CH);
           }
         }
+        // the first V fragments are requested now, so that they arrive behind the softmax arithmetic
+        bf16x8 vb[2][CH];
+#pragma unroll
+        for (int i = 0; i < CH; ++i) vb[0][i] = fragV(i);
+        __builtin_amdgcn_sched_barrier(0);
         float tmax = -INFINITY;          // row maximum of the raw scores (the scale is positive, so it commutes with max)
         if (kv0 + 63 > qw0) {          // wave-uniform: some (key, query) pair of the tile is masked
 #pragma unroll
@@ -267,24 +280,21 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
         bf16x8 pf[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) pf[t] = pack8(sacc[t >> 1], 8 * (t & 1));
-        {          // steps run over (t, c) with c fastest: consecutive MFMAs hit different accumulators
+        {          // steps n run over (t, c) with c fastest: consecutive MFMAs hit different accumulators
           __builtin_amdgcn_sched_barrier(0);
-          bf16x8 vb[2];
-          vb[0] = frag<8>(vtile, l32, lh);
-          vb[1] = frag<8>(vtile, (1 % CT) * 32 + l32, 2 * (1 / CT) + lh);
 #pragma unroll
-          for (int sp = 0; sp < 2 * CT; ++sp) {          // two (t, c) steps per fence: 2 reads ahead, 2 MFMAs
+          for (int c = 0; c < 4 * CT / CH; ++c) {
             PP_STEP_BEGIN();
-            bf16x8 cur0 = vb[0], cur1 = vb[1];
-            if (sp + 1 < 2 * CT) {
-              const int n0 = 2 * sp + 2, n1 = 2 * sp + 3;
-              vb[0] = frag<8>(vtile, (n0 % CT) * 32 + l32, 2 * (n0 / CT) + lh);
-              vb[1] = frag<8>(vtile, (n1 % CT) * 32 + l32, 2 * (n1 / CT) + lh);
+            if (c + 1 < 4 * CT / CH) {
+#pragma unroll
+              for (int i = 0; i < CH; ++i) vb[(c + 1) & 1][i] = fragV((c + 1) * CH + i);
             }
-            const int a0 = 2 * sp, a1 = 2 * sp + 1;
-            oacc[a0 % CT] = MFMA(cur0, pf[a0 / CT], oacc[a0 % CT]);
-            oacc[a1 % CT] = MFMA(cur1, pf[a1 / CT], oacc[a1 % CT]);
-            PP_READS_THEN_MFMAS(2, 2);
+#pragma unroll
+            for (int i = 0; i < CH; ++i) {
+              const int n = c * CH + i;
+              oacc[n % CT] = MFMA(vb[c & 1][i], pf[n / CT], oacc[n % CT]);
+            }
+            PP_READS_THEN_MFMAS(CH, CH);
           }
         }
       }

@@ -177,6 +177,7 @@ struct GemmTimer {          // brackets the launches issued during its lifetime
     idx = m->ev_used; m->ev_used += 2; on = true;
     hipEventRecord(m->ev[idx], m->st);
   }
+  void cancel() { if (on) { on = false; m->ev_used -= 2; } }          // nothing was launched: give the event pair back
   ~GemmTimer() { if (on) { hipEventRecord(m->ev[idx + 1], m->st); m->timed_flops += flops; } }
 };
 }  // namespace
@@ -459,6 +460,24 @@ static void gemm_nt(pp_model* m, const void* A, int lda, const void* B, int ldb,
   k_gemm_nt_plain(m->st, m->cfg.dtype, A, lda, B, ldb, C, ldc, M, N, K, epi, R, 0);
 }
 
+// gate/up projection with the SwiGLU product formed in the GEMM's epilogue; false = not launched (shape or path)
+static bool gemm_swiglu(pp_model* m, const void* X, const void* Wgu, void* gu, void* a, int T, int F, int d) {
+  if (m->cfg.dtype != PP_BF16 || m->force_plain) return false;
+  GemmTimer timer(m, 2.0 * T * (2.0 * F) * d);
+  if (k_gemm_swiglu_fwd_mfma(m->st, X, d, Wgu, d, gu, a, T, F, d) != 0) { timer.cancel(); return false; }
+  if (m->flop_acc) *m->flop_acc += 2.0 * T * (2.0 * F) * d;
+  return true;
+}
+
+// dA = G Wd_rows^T with the SwiGLU backward formed in the epilogue (dA itself is never stored); false = not launched
+static bool gemm_swiglu_bwd(pp_model* m, const void* G, const void* Wd_rows, const void* gu_c0, void* dgu_c0, int T, int nc, int F, int d) {
+  if (m->cfg.dtype != PP_BF16 || m->force_plain) return false;
+  GemmTimer timer(m, 2.0 * T * (double)nc * d);
+  if (k_gemm_swiglu_bwd_mfma(m->st, G, d, Wd_rows, d, gu_c0, dgu_c0, 2 * F, F, T, nc, d) != 0) { timer.cancel(); return false; }
+  if (m->flop_acc) *m->flop_acc += 2.0 * T * (double)nc * d;
+  return true;
+}
+
 // Weight-gradient GEMM: G[M x N] (fp32, ld = N) = At[M x K] * Bt[N x K]^T with K = tokens.  Few output tiles and
 // a long K: the K range is split over `splits` workgroup columns and summed in fixed order.
 static void gemm_dw(pp_model* m, const void* At, const void* Bt, float* G, int M, int N, int K) {
@@ -532,8 +551,10 @@ extern "C" int pp_local_step(pp_model* m, const int32_t* tokens_dev, const int32
     attn_fwd(m, act(l, w.a_qkv), act(l, w.a_o), (float*)act(l, w.a_lse), B, S);
     gemm_nt(m, act(l, w.a_o), d, canon(lb + ly.o_wo), d, act(l, w.a_xm), d, T, d, d, EPI_ADD_RES, x);
     k_rmsnorm_fwd(st, dt, act(l, w.a_xm), canon(lb + ly.o_ffn_norm), act(l, w.a_n2), (float*)act(l, w.a_rstd2), T, d, c.rms_eps);
-    gemm_nt(m, act(l, w.a_n2), d, canon(lb + ly.o_wg), d, act(l, w.a_gu), 2 * F, T, 2 * F, d);      // [Wg; Wu] are adjacent
-    k_swiglu_fwd(st, dt, act(l, w.a_gu), act(l, w.a_a), T, F);
+    if (!gemm_swiglu(m, act(l, w.a_n2), canon(lb + ly.o_wg), act(l, w.a_gu), act(l, w.a_a), T, F, d)) {      // [Wg; Wu] are adjacent
+      gemm_nt(m, act(l, w.a_n2), d, canon(lb + ly.o_wg), d, act(l, w.a_gu), 2 * F, T, 2 * F, d);
+      k_swiglu_fwd(st, dt, act(l, w.a_gu), act(l, w.a_a), T, F);
+    }
     gemm_nt(m, act(l, w.a_a), F, shad(sb + ly.sh_wd), F, xnext, d, T, d, F, EPI_ADD_RES, act(l, w.a_xm));
   }
   void* xL = W + w.xL;
@@ -586,8 +607,10 @@ extern "C" int pp_local_step(pp_model* m, const int32_t* tokens_dev, const int32
             k_transpose(st, dt, dx, d, tB, T, T, d);
             gemm_dw(m, tA, tB, g + find_seg(m, TK_WD, l)->packed_off, Fk, d, T);
           }
-          gemm_nt(m, dx, d, canon(lb + ly.o_wd + (int64_t)c0 * d), d, dA, nc, T, nc, d);        // dA = G Wd^T (rows c0..c1 of Wd)
-          k_swiglu_bwd(st, dt, act(l, w.a_gu), dA, nc, dgu, T, F, c0, c1);
+          if (!gemm_swiglu_bwd(m, dx, canon(lb + ly.o_wd + (int64_t)c0 * d), ofs(act(l, w.a_gu), c0), ofs(dgu, c0), T, nc, F, d)) {
+            gemm_nt(m, dx, d, canon(lb + ly.o_wd + (int64_t)c0 * d), d, dA, nc, T, nc, d);        // dA = G Wd^T (rows c0..c1 of Wd)
+            k_swiglu_bwd(st, dt, act(l, w.a_gu), dA, nc, dgu, T, F, c0, c1);
+          }
           if (mk.ffn) {      // [dWg_k; dWu_k] = [dG_k; dU_k]^T Xn
             k_transpose(st, dt, ofs(dgu, mk.fl), 2 * F, tA, T, T, Fk);
             k_transpose(st, dt, ofs(dgu, (size_t)F + mk.fl), 2 * F, ofs(tA, (size_t)Fk * T), T, T, Fk);

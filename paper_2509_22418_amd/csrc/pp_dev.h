@@ -44,6 +44,11 @@ __device__ __forceinline__ void store8(bf16_t* p, const float v[8]) {
   *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
+// logistic function and the SwiGLU product with the hardware reciprocal (1 ulp): shared by the stand-alone SwiGLU
+// kernels and the GEMM epilogue that fuses them, so that both paths give identical values
+__device__ __forceinline__ float sigmoid_fast(float x) { return __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
+__device__ __forceinline__ float silu_mul(float g, float u) { return g * sigmoid_fast(g) * u; }
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);

@@ -186,7 +186,7 @@ static_assert(BM == 256 && BN == 256, "unit geometry assumes 256-row panels");
 template <int EPI, bool OUT_F32>
 __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ B, int ldb,
                                                                void* Cv, int ldc, int M, int N, int Ksplit, const bf16_t* __restrict__ R,
-                                                               int tiles_m, int tiles_n) {
+                                                               int tiles_m, int tiles_n, int ldc2) {
   extern __shared__ u32x4 lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -213,7 +213,14 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
     const int row = wave * 32 + i * 8 + (lane >> 3);
     const int c = (lane & 7) ^ ((row >> 1) & 7);
     gA[i] = A + (size_t)min(m0 + row, M - 1) * lda + kbase + c * 8;
-    gB[i] = B + (size_t)min(n0 + row, N - 1) * ldb + kbase + c * 8;
+    if constexpr (EPI == EPI_SWIGLU) {
+      // panel rows 64q .. 64q+31 are rows of W_g, 64q+32 .. 64q+63 the same hidden units' rows of W_u (N = d_ff,
+      // B = [W_g; W_u]): a wave's 64 output columns then hold gate and up of 32 units in matching registers
+      const int unit = min(tn * (BN / 2) + (row >> 6) * 32 + (row & 31), N - 1);
+      gB[i] = B + ((size_t)((row >> 5) & 1) * N + unit) * ldb + kbase + c * 8;
+    } else {
+      gB[i] = B + (size_t)min(n0 + row, N - 1) * ldb + kbase + c * 8;
+    }
   }
   const int wdst = wave * 32 * 8;          // chunk offset of this wave's rows inside a unit (wave-uniform)
   const int ns = Ksplit / DL_BK;
@@ -298,6 +305,62 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
 #undef PP_DL_INTERLEAVE
   __builtin_amdgcn_s_waitcnt(0x0F70);              // drain the clamped tail loads before the LDS is released
 
+  if constexpr (EPI == EPI_SWIGLU) {
+    // ---- fused SwiGLU epilogue.  acc[i][0] / acc[i][1] are gate and up pre-activations of hidden unit
+    // u0 + 8*(r/4) + 4*(lane/32) + r%4 (u0 = tn*128 + wn*32) for output row m0 + wm*128 + i*32 + lane%32.  Both are
+    // rounded to bf16 and stored at columns u and N + u of C (ldc >= 2 N); a = silu(g) * u is formed from the ROUNDED
+    // values -- exactly what a separate pass over the stored matrix would compute -- and stored at column u of C2.
+    // Each wave turns 64 rows at a time around in a private 16 KB LDS patch (64 rows x 256 bytes: gate | up | a | unused,
+    // 16-byte piece p of row r at p ^ (r & 15)), so that 4 lanes cover one 64-byte row segment of each output.
+    __builtin_amdgcn_s_waitcnt(0x0070);
+    __builtin_amdgcn_s_barrier();                  // every wave is done with the staged panels
+    bf16_t* C = reinterpret_cast<bf16_t*>(Cv);
+    bf16_t* C2 = const_cast<bf16_t*>(R);
+    char* wbase = reinterpret_cast<char*>(lds) + wave * 16384;
+    const int u0 = tn * (BN / 2) + wn * 32;
+#pragma unroll
+    for (int hi = 0; hi < 2; ++hi) {
+#pragma unroll
+      for (int ii = 0; ii < 2; ++ii) {
+        const int i = 2 * hi + ii, row = ii * 32 + l32;
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          uint2 wg, wu, wa;
+          wg.x = f32x2_to_bf16x2(acc[i][0][4 * g4], acc[i][0][4 * g4 + 1]);
+          wg.y = f32x2_to_bf16x2(acc[i][0][4 * g4 + 2], acc[i][0][4 * g4 + 3]);
+          wu.x = f32x2_to_bf16x2(acc[i][1][4 * g4], acc[i][1][4 * g4 + 1]);
+          wu.y = f32x2_to_bf16x2(acc[i][1][4 * g4 + 2], acc[i][1][4 * g4 + 3]);
+          const float gr[4] = {__uint_as_float(wg.x << 16), __uint_as_float(wg.x & 0xffff0000u), __uint_as_float(wg.y << 16), __uint_as_float(wg.y & 0xffff0000u)};
+          const float ur[4] = {__uint_as_float(wu.x << 16), __uint_as_float(wu.x & 0xffff0000u), __uint_as_float(wu.y << 16), __uint_as_float(wu.y & 0xffff0000u)};
+          float av[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) av[e] = silu_mul(gr[e], ur[e]);
+          wa.x = f32x2_to_bf16x2(av[0], av[1]);
+          wa.y = f32x2_to_bf16x2(av[2], av[3]);
+          // 8-byte piece (2*g4 + lhi) of the 64-byte segment: 16-byte piece g4, half lhi
+          char* rowp = wbase + row * 256 + lhi * 8;
+          *reinterpret_cast<uint2*>(rowp + (((0 + g4) ^ (row & 15)) << 4)) = wg;
+          *reinterpret_cast<uint2*>(rowp + (((4 + g4) ^ (row & 15)) << 4)) = wu;
+          *reinterpret_cast<uint2*>(rowp + (((8 + g4) ^ (row & 15)) << 4)) = wa;
+        }
+      }
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {          // gate and up: 8 pieces per row, 8 rows per wave instruction
+        const int row = 8 * it + (lane >> 3), pc = lane & 7;
+        const uint4 v = *reinterpret_cast<const uint4*>(wbase + row * 256 + ((pc ^ (row & 15)) << 4));
+        const int grow = m0 + wm * 128 + hi * 64 + row, unit = u0 + (pc & 3) * 8;
+        if (grow < M && unit < N) *reinterpret_cast<uint4*>(C + (size_t)grow * ldc + (size_t)(pc >> 2) * N + unit) = v;
+      }
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {          // a: 4 pieces per row, 16 rows per wave instruction
+        const int row = 16 * it + (lane >> 2), pc = 8 + (lane & 3);
+        const uint4 v = *reinterpret_cast<const uint4*>(wbase + row * 256 + ((pc ^ (row & 15)) << 4));
+        const int grow = m0 + wm * 128 + hi * 64 + row, unit = u0 + (lane & 3) * 8;
+        if (grow < M && unit < N) *reinterpret_cast<uint4*>(C2 + (size_t)grow * ldc2 + unit) = v;
+      }
+    }
+    return;
+  }
   // ---- epilogue: element r of accumulator (i, j) is output row m0 + wm*128 + i*32 + lane%32,
   //      column n0 + wn*64 + j*32 + 8*(r/4) + 4*(lane/32) + r%4
   if constexpr (!OUT_F32) {
@@ -335,7 +398,7 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
           }
         }
       } else {
-        // residual add: the sum is formed in fp32 and rounded once, so the patch holds floats (64 rows x 256 bytes,
+        // residual add (or SwiGLU backward): the result is formed in fp32 and rounded once, so the patch holds floats (64 rows x 256 bytes,
         // 16-byte piece p of row r at p ^ (r & 15)); 16 lanes then cover one 128-byte row segment of R and of C
         char* wbase = reinterpret_cast<char*>(lds) + wave * 16384;
 #pragma unroll
@@ -360,10 +423,31 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
             if (grow < M && gcol < N) {
               const size_t off = (size_t)grow * ldc + gcol;
               const uint2 rr = *reinterpret_cast<const uint2*>(R + off);
-              uint2 w;
-              w.x = f32x2_to_bf16x2(v.x + __uint_as_float(rr.x << 16), v.y + __uint_as_float(rr.x & 0xffff0000u));
-              w.y = f32x2_to_bf16x2(v.z + __uint_as_float(rr.y << 16), v.w + __uint_as_float(rr.y & 0xffff0000u));
-              *reinterpret_cast<uint2*>(C + off) = w;
+              if constexpr (EPI == EPI_SWIGLU_BWD) {
+                // the product is dL/da; R holds the saved gate at this column and the saved up ldc2 columns further on:
+                // dg = da u sig(g) (1 + g (1 - sig(g))) and du = da g sig(g) go to the same two places of C
+                const uint2 ru = *reinterpret_cast<const uint2*>(R + off + ldc2);
+                const float da[4] = {v.x, v.y, v.z, v.w};
+                const float gg[4] = {__uint_as_float(rr.x << 16), __uint_as_float(rr.x & 0xffff0000u), __uint_as_float(rr.y << 16), __uint_as_float(rr.y & 0xffff0000u)};
+                const float uu[4] = {__uint_as_float(ru.x << 16), __uint_as_float(ru.x & 0xffff0000u), __uint_as_float(ru.y << 16), __uint_as_float(ru.y & 0xffff0000u)};
+                float dg[4], du[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                  const float sg = sigmoid_fast(gg[e]);
+                  du[e] = da[e] * gg[e] * sg;
+                  dg[e] = da[e] * uu[e] * sg * (1.0f + gg[e] * (1.0f - sg));
+                }
+                uint2 w;
+                w.x = f32x2_to_bf16x2(dg[0], dg[1]); w.y = f32x2_to_bf16x2(dg[2], dg[3]);
+                *reinterpret_cast<uint2*>(C + off) = w;
+                w.x = f32x2_to_bf16x2(du[0], du[1]); w.y = f32x2_to_bf16x2(du[2], du[3]);
+                *reinterpret_cast<uint2*>(C + off + ldc2) = w;
+              } else {
+                uint2 w;
+                w.x = f32x2_to_bf16x2(v.x + __uint_as_float(rr.x << 16), v.y + __uint_as_float(rr.x & 0xffff0000u));
+                w.y = f32x2_to_bf16x2(v.z + __uint_as_float(rr.y << 16), v.w + __uint_as_float(rr.y & 0xffff0000u));
+                *reinterpret_cast<uint2*>(C + off) = w;
+              }
             }
           }
         }
@@ -414,7 +498,39 @@ static int launch_dl(hipStream_t st, const void* A, int lda, const void* B, int 
   }
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   dim3 grid(tiles_m * tiles_n, splits);
-  kern<<<grid, 512, DL_LDS_BYTES, st>>>((const bf16_t*)A, lda, (const bf16_t*)B, ldb, C, ldc, M, N, Ksplit, (const bf16_t*)R, tiles_m, tiles_n);
+  kern<<<grid, 512, DL_LDS_BYTES, st>>>((const bf16_t*)A, lda, (const bf16_t*)B, ldb, C, ldc, M, N, Ksplit, (const bf16_t*)R, tiles_m, tiles_n, 0);
+  return 0;
+}
+
+// gu[M x 2F] (ld 2F) = X[M x K] [Wg; Wu]^T and a[M x F] = silu(gate) * up in one launch; Wgu = the 2F x K stack
+int k_gemm_swiglu_fwd_mfma(hipStream_t st, const void* X, int ldx, const void* Wgu, int ldw, void* gu, void* a, int M, int F, int K) {
+  if (g_gemm_variant != 1 || M < 1 || F < 8 || (F & 7) || K < DL_BK || K % DL_BK || (ldx & 7) || (ldw & 7)) return 1;
+  if (((uintptr_t)X | (uintptr_t)Wgu | (uintptr_t)gu | (uintptr_t)a) & 15) return 1;
+  static bool attr_done = false;
+  auto kern = gemm_nt_mfma_dl_kernel<EPI_SWIGLU, false>;
+  if (!attr_done) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, DL_LDS_BYTES) != hipSuccess) return 1;
+    attr_done = true;
+  }
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (F + BN / 2 - 1) / (BN / 2);
+  kern<<<dim3(tiles_m * tiles_n, 1), 512, DL_LDS_BYTES, st>>>((const bf16_t*)X, ldx, (const bf16_t*)Wgu, ldw, gu, 2 * F, M, F, K, (const bf16_t*)a, tiles_m, tiles_n, F);
+  return 0;
+}
+
+// dgu[M x 2F] (columns c .. and F + c ..) from dA = G Wd_rows^T without materialising dA: C = dgu + c0, R = gu + c0, both
+// with leading dimension ld2f = 2F; N = number of hidden units (rows of Wd_rows), half = F
+int k_gemm_swiglu_bwd_mfma(hipStream_t st, const void* G, int ldg, const void* Wd_rows, int ldw, const void* gu_c0, void* dgu_c0, int ld2f, int half,
+                           int M, int N, int K) {
+  if (g_gemm_variant != 1 || M < 1 || N < 8 || (N & 7) || (ld2f & 7) || (half & 7) || K < DL_BK || K % DL_BK || (ldg & 7) || (ldw & 7)) return 1;
+  if (((uintptr_t)G | (uintptr_t)Wd_rows | (uintptr_t)gu_c0 | (uintptr_t)dgu_c0) & 15) return 1;
+  static bool attr_done = false;
+  auto kern = gemm_nt_mfma_dl_kernel<EPI_SWIGLU_BWD, false>;
+  if (!attr_done) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, DL_LDS_BYTES) != hipSuccess) return 1;
+    attr_done = true;
+  }
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  kern<<<dim3(tiles_m * tiles_n, 1), 512, DL_LDS_BYTES, st>>>((const bf16_t*)G, ldg, (const bf16_t*)Wd_rows, ldw, dgu_c0, ld2f, M, N, K, (const bf16_t*)gu_c0, tiles_m, tiles_n, half);
   return 0;
 }
 

@@ -18,7 +18,7 @@ struct ShadowSeg {      // one trainable row block that also lives, transposed, 
   int32_t rows, cols, shadow_ld, tile_start;   // tile_start: first 64x64 tile index of this block in the batched launch
 };
 
-enum { EPI_STORE = 0, EPI_ADD_RES = 1 };
+enum { EPI_STORE = 0, EPI_ADD_RES = 1, EPI_SWIGLU = 2, EPI_SWIGLU_BWD = 3 };          // the last two: only inside k_gemm_swiglu_*_mfma
 
 void k_fill_f32(hipStream_t st, float* p, size_t n, float v);
 void k_rope_tables(hipStream_t st, float* cosb, float* sinb, int S, int dh, float base);
@@ -65,6 +65,12 @@ void k_outer(hipStream_t st, int dtype, void* params, const RowInfo* rows, float
 void k_synth_delta_sum(hipStream_t st, float* dst, size_t n, const uint64_t* keys_dev, int n_nodes, float std);
 
 // MFMA paths (bf16 only).  Return 0 if launched, 1 if the shape is not supported (caller falls back).
+// gu[M x 2F] = X [Wg; Wu]^T (bf16, ld 2F) and a[M x F] = silu(gate) * up from the rounded gate / up, one launch.
+// Returns non-zero (nothing launched) when the shapes do not fit; the caller then runs the GEMM and k_swiglu_fwd.
+int k_gemm_swiglu_fwd_mfma(hipStream_t st, const void* X, int ldx, const void* Wgu, int ldw, void* gu, void* a, int M, int F, int K);
+// dgu columns c0.. and F + c0.. from the product G Wd_rows^T (= dL/da for N hidden units) and the saved gate / up; see the definition
+int k_gemm_swiglu_bwd_mfma(hipStream_t st, const void* G, int ldg, const void* Wd_rows, int ldw, const void* gu_c0, void* dgu_c0, int ld2f, int half,
+                           int M, int N, int K);
 int k_gemm_nt_mfma(hipStream_t st, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
                    int epi, const void* R, int out_f32, int splits, float* partial);
 void gemm_set_variant(int v);          // 0: register-staged MFMA GEMM, 1: direct-to-LDS MFMA GEMM

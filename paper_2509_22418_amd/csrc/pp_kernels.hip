@@ -226,7 +226,7 @@ __global__ void swiglu_fwd_kernel(const T* __restrict__ gu, T* __restrict__ a, i
   load8(gu + t * (size_t)(2 * F) + c, g);
   load8(gu + t * (size_t)(2 * F) + F + c, u);
 #pragma unroll
-  for (int k = 0; k < 8; ++k) g[k] = g[k] / (1.0f + __expf(-g[k])) * u[k];
+  for (int k = 0; k < 8; ++k) g[k] = silu_mul(g[k], u[k]);
   store8(a + t * (size_t)F + c, g);
 }
 void k_swiglu_fwd(hipStream_t st, int dtype, const void* gu, void* a, int T_, int F) {
@@ -249,7 +249,7 @@ __global__ void swiglu_bwd_kernel(const T* __restrict__ gu, const T* __restrict_
   load8(dA + t * (size_t)ldA + cc, da);
 #pragma unroll
   for (int k = 0; k < 8; ++k) {
-    const float sg = 1.0f / (1.0f + __expf(-g[k]));
+    const float sg = sigmoid_fast(g[k]);
     du[k] = da[k] * g[k] * sg;
     dg[k] = da[k] * u[k] * sg * (1.0f + g[k] * (1.0f - sg));
   }

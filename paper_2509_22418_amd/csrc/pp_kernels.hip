@@ -57,37 +57,68 @@ void k_embed(hipStream_t st, int dtype, const int32_t* tok, const void* E, void*
 }
 
 // ------------------------------------------------------------------------------------------ RMSNorm
-// One wave per row, 4 rows per block; lanes stride over the row in 8-element vectors.
-template <class T>
+// One wave per row, 4 rows per block; lanes stride over the row in 8-element vectors.  NV > 0: the row has exactly
+// NV * 512 elements and stays in registers between the reduction and the output pass (one read of every input);
+// NV == 0: any d (multiple of 8), two passes over the inputs.  Both orders of summation are the same.
+template <class T, int NV>
 __global__ void rmsnorm_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma, T* __restrict__ y,
                                    float* __restrict__ rstd_out, int T_, int d, float eps) {
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (row >= T_) return;
   const T* xr = x + (size_t)row * d;
-  float ss = 0.f, v[8], g[8];
-  for (int c = lane * 8; c < d; c += 512) {
-    load8(xr + c, v);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) ss += v[i] * v[i];
-  }
-  ss = wave_sum(ss);
-  const float rstd = 1.0f / sqrtf(ss / (float)d + eps);
-  if (lane == 0) rstd_out[row] = rstd;
   T* yr = y + (size_t)row * d;
-  for (int c = lane * 8; c < d; c += 512) {
-    load8(xr + c, v);
-    load8(gamma + c, g);
+  float ss = 0.f, g[8];
+  if constexpr (NV > 0) {
+    float v[NV][8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] = v[i] * rstd * g[i];
-    store8(yr + c, v);
+    for (int k = 0; k < NV; ++k) load8(xr + lane * 8 + k * 512, v[k]);
+#pragma unroll
+    for (int k = 0; k < NV; ++k)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) ss += v[k][i] * v[k][i];
+    ss = wave_sum(ss);
+    const float rstd = 1.0f / sqrtf(ss / (float)d + eps);
+    if (lane == 0) rstd_out[row] = rstd;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      load8(gamma + lane * 8 + k * 512, g);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[k][i] = v[k][i] * rstd * g[i];
+      store8(yr + lane * 8 + k * 512, v[k]);
+    }
+  } else {
+    float v[8];
+    for (int c = lane * 8; c < d; c += 512) {
+      load8(xr + c, v);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) ss += v[i] * v[i];
+    }
+    ss = wave_sum(ss);
+    const float rstd = 1.0f / sqrtf(ss / (float)d + eps);
+    if (lane == 0) rstd_out[row] = rstd;
+    for (int c = lane * 8; c < d; c += 512) {
+      load8(xr + c, v);
+      load8(gamma + c, g);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = v[i] * rstd * g[i];
+      store8(yr + c, v);
+    }
   }
 }
+#define PP_RMS_NV(d, CALL)                                              \
+  do {                                                                  \
+    if ((d) == 2048) { constexpr int NV = 4; CALL; }                    \
+    else if ((d) == 1024) { constexpr int NV = 2; CALL; }               \
+    else if ((d) == 4096) { constexpr int NV = 8; CALL; }               \
+    else if ((d) == 512) { constexpr int NV = 1; CALL; }                \
+    else { constexpr int NV = 0; CALL; }                                \
+  } while (0)
 void k_rmsnorm_fwd(hipStream_t st, int dtype, const void* x, const void* gamma, void* y, float* rstd, int T_, int d, float eps) {
-  PP_DISPATCH(dtype, rmsnorm_fwd_kernel<T><<<cdiv(T_, 4), 256, 0, st>>>((const T*)x, (const T*)gamma, (T*)y, rstd, T_, d, eps));
+  PP_RMS_NV(d, PP_DISPATCH(dtype, (rmsnorm_fwd_kernel<T, NV><<<cdiv(T_, 4), 256, 0, st>>>((const T*)x, (const T*)gamma, (T*)y, rstd, T_, d, eps))));
 }
 
-template <class T>
+template <class T, int NV>
 __global__ void rmsnorm_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x, const float* __restrict__ rstd_in,
                                    const T* __restrict__ gamma, const T* dres, T* dx, int T_, int d) {
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -95,32 +126,59 @@ __global__ void rmsnorm_bwd_kernel(const T* __restrict__ dy, const T* __restrict
   if (row >= T_) return;
   const size_t off = (size_t)row * d;
   const float rstd = rstd_in[row];
-  float dot = 0.f, a[8], b[8], g[8], r[8];
-  for (int c = lane * 8; c < d; c += 512) {
-    load8(dy + off + c, a);
-    load8(x + off + c, b);
-    load8(gamma + c, g);
+  float dot = 0.f, g[8], r[8];
+  if constexpr (NV > 0) {
+    float a[NV][8], b[NV][8];          // a: gamma * dy, b: x
 #pragma unroll
-    for (int i = 0; i < 8; ++i) dot += a[i] * g[i] * b[i];
-  }
-  dot = wave_sum(dot) * rstd / (float)d;      // mean(gamma*dy*xhat)
-  for (int c = lane * 8; c < d; c += 512) {
-    load8(dy + off + c, a);
-    load8(x + off + c, b);
-    load8(gamma + c, g);
-    if (dres) load8(dres + off + c, r);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      float val = rstd * (a[i] * g[i] - b[i] * rstd * dot);
-      a[i] = dres ? val + r[i] : val;
+    for (int k = 0; k < NV; ++k) {
+      load8(dy + off + lane * 8 + k * 512, a[k]);
+      load8(x + off + lane * 8 + k * 512, b[k]);
     }
-    store8(dx + off + c, a);
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      load8(gamma + lane * 8 + k * 512, g);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { a[k][i] *= g[i]; dot += a[k][i] * b[k][i]; }
+    }
+    dot = wave_sum(dot) * rstd / (float)d;      // mean(gamma*dy*xhat)
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      if (dres) load8(dres + off + lane * 8 + k * 512, r);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float val = rstd * (a[k][i] - b[k][i] * rstd * dot);
+        a[k][i] = dres ? val + r[i] : val;
+      }
+      store8(dx + off + lane * 8 + k * 512, a[k]);
+    }
+  } else {
+    float a[8], b[8];
+    for (int c = lane * 8; c < d; c += 512) {
+      load8(dy + off + c, a);
+      load8(x + off + c, b);
+      load8(gamma + c, g);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { a[i] *= g[i]; dot += a[i] * b[i]; }
+    }
+    dot = wave_sum(dot) * rstd / (float)d;      // mean(gamma*dy*xhat)
+    for (int c = lane * 8; c < d; c += 512) {
+      load8(dy + off + c, a);
+      load8(x + off + c, b);
+      load8(gamma + c, g);
+      if (dres) load8(dres + off + c, r);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float val = rstd * (a[i] * g[i] - b[i] * rstd * dot);
+        a[i] = dres ? val + r[i] : val;
+      }
+      store8(dx + off + c, a);
+    }
   }
 }
 void k_rmsnorm_bwd(hipStream_t st, int dtype, const void* dy, const void* x, const float* rstd, const void* gamma,
                    const void* dres, void* dx, int T_, int d) {
-  PP_DISPATCH(dtype, rmsnorm_bwd_kernel<T><<<cdiv(T_, 4), 256, 0, st>>>((const T*)dy, (const T*)x, rstd, (const T*)gamma,
-                                                                         (const T*)dres, (T*)dx, T_, d));
+  PP_RMS_NV(d, PP_DISPATCH(dtype, (rmsnorm_bwd_kernel<T, NV><<<cdiv(T_, 4), 256, 0, st>>>((const T*)dy, (const T*)x, rstd, (const T*)gamma,
+                                                                                          (const T*)dres, (T*)dx, T_, d))));
 }
 
 // dgamma: stage 1 -- block (64 columns) x (row chunk b of 64) sums its rows in fixed order; stage 2 sums the 64 chunks.

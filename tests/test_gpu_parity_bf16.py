@@ -143,3 +143,13 @@ def test_fused_gate_up_activation_matches_stored_projections_and_oracle():
             assert cosine(got.ravel(), ref.ravel()) >= 0.9995, (l, name)
             assert np.max(np.abs(got - ref)) <= 0.05 * np.max(np.abs(ref)) + 1e-6, (l, name)
     m.close()
+
+
+@pytest.mark.parametrize("d_model", [512, 1024, 4096])
+def test_register_resident_rmsnorm_widths_match_oracle(d_model):
+    """RMSNorm keeps a row in registers for d = 512, 1024, 2048 and 4096 (one specialisation each; 2048 is the 1.3B
+    shape, covered above).  One-layer models of the other widths, all parameters trainable so that forward, backward
+    and the gain gradients of every norm enter the comparison."""
+    cfg = gen.make_config("tiny", n_layers=1, d_model=d_model, n_heads=d_model // 128, d_ff=512, vocab=512, batch=1, seq=72, dtype="bf16")
+    print(f"case rmsnorm-width d={d_model}", flush=True)
+    run_case(cfg, dict(all=1), seed=31)

@@ -181,17 +181,19 @@ def main():
     log(f"[bench] weights generated in {time.perf_counter() - t0:.1f} s")
     batches = [gen.make_tokens(cfg, args.seed, step=i) for i in range(4)]
 
-    legs = [("rho=1/%d" % n_slices, gen.ffn_slice_mask(cfg, 0, n_slices), 1.0 / n_slices)]
+    legs = [("rho=1/%d" % n_slices, gen.ffn_slice_mask(cfg, 0, n_slices), 1.0 / n_slices, cfg)]
     if args.legs == "all":
-        legs.append(("rho=1/8", gen.ffn_slice_mask(cfg, 0, 8), 1.0 / 8))
-        legs.append(("all-trainable", dict(all=1), 1.0))
+        legs.append(("rho=1/8", gen.ffn_slice_mask(cfg, 0, 8), 1.0 / 8, cfg))
+        legs.append(("all-trainable", dict(all=1), 1.0, cfg))
         if n_slices == 8:
             legs.pop(1)
+        # the paper's memory regime: full activation recomputation (same results bit for bit, less workspace, more time)
+        legs.append(("rho=1/%d+recompute" % n_slices, gen.ffn_slice_mask(cfg, 0, n_slices), 1.0 / n_slices, dict(cfg, recompute=1)))
     results = {}
     outer_step = None
-    for name, mask, rho in legs:
+    for name, mask, rho, leg_cfg in legs:
         t1 = time.perf_counter()
-        r = run_leg(torch, pp, gen, cfg, weights, mask, batches, args.steps, args.warmup, time_gemm=True,
+        r = run_leg(torch, pp, gen, leg_cfg, weights, mask, batches, args.steps, args.warmup, time_gemm=True,
                     outer=(name == legs[0][0]), seed=args.seed)
         fwd, bwd = closed_form_flops(cfg, B, S, rho)
         ms = r["seconds"] / args.steps * 1e3

@@ -53,6 +53,10 @@ typedef struct {
   int32_t max_batch, max_seq; /* largest B and S any pp_local_step call will use */
   int32_t dtype;              /* PP_F32: fp32 storage and arithmetic; PP_BF16: bf16 storage, fp32 accumulate */
   float rms_eps, rope_base;
+  int32_t recompute;          /* 0: every layer's activations are kept for the backward pass.  1: full activation
+                                 recomputation (the memory regime of the paper's Table 1): only each layer's input is
+                                 kept, the layer is run forward again when the backward pass reaches it.  Same results
+                                 bit for bit; WORKSPACE shrinks by about (n_layers - 1) layers of activations. */
 } pp_config;
 
 /* I_train of Algorithm 1 as a union of row blocks (Section "Parameter Slicing").
@@ -97,7 +101,8 @@ int pp_init_model(const pp_config* cfg, void* params_dev, size_t params_bytes, v
  * fp32 subset, valid after pp_set_trainable_mask / a step), "state.rows" (int64 canonical element
  * offset of every packed row of d_model elements), "shadow.<weight>" (the transposed read-only copy of wqkv, wo,
  * wd or lm_head, shape [in x out]) and, for debugging, "dbg.<buffer>[.<layer>]" taps into the workspace
- * (x, n1, qkv, o, xm, n2, gu, a, lse per layer; xL, logits, dx, dn, dqkv, dgu), sized for max_batch*max_seq tokens.
+ * (x, n1, qkv, o, xm, n2, gu, a, lse per layer; xL, logits, dx, dn, dqkv, dgu), sized for max_batch*max_seq tokens;
+ * with recompute = 1 only x is per layer, the others show the layer worked on last.
  * Both block until the copy is done.
  * pp_set_tensor on a weight after pp_set_trainable_mask leaves the fp32 masters stale: set the mask again. */
 int pp_set_tensor(pp_model* m, const char* name, const void* host_src, size_t bytes);
@@ -126,6 +131,13 @@ int pp_local_step(pp_model* m, const int32_t* tokens_dev, const int32_t* targets
  * from the new global values: weights and fp32 masters <- theta_g, m and v are kept.  Asynchronous. */
 int pp_outer_delta(pp_model* m, float* theta_g_dev, float* momentum_dev, const float* others_sum_dev,
                    const pp_outer* opt, float* delta_out_dev);
+
+/* The same step for one group of the streaming synchronisation (Experimental Setup: the 24 layers are synchronised in
+ * groups, one group every H steps, plus a group with the embeddings and the output norm): only the packed elements of
+ * layers [layer_lo, layer_hi) and, if ends != 0, of embed / final_norm / lm_head are read or written; every buffer is still
+ * indexed as in pp_outer_delta (full packed length n), the rest of it is left untouched.  Asynchronous. */
+int pp_outer_delta_group(pp_model* m, int32_t layer_lo, int32_t layer_hi, int32_t ends, float* theta_g_dev, float* momentum_dev,
+                         const float* others_sum_dev, const pp_outer* opt, float* delta_out_dev);
 
 /* Fills dst_dev[0..n) with the sum of n_nodes seeded N(0, std) vectors from the counter-based generator
  * (splitmix64 finaliser over key + index*golden, Box-Muller pairs); stands for the all-reduced deltas of

@@ -14,7 +14,7 @@ import numpy as np
 PP_F32, PP_BF16 = 0, 1
 PP_BYTES_PARAMS, PP_BYTES_STATE, PP_BYTES_WORKSPACE, PP_BYTES_SHADOW, PP_BYTES_ACTIVATIONS = range(5)
 EXPORTS = ["pp_query_bytes", "pp_init_model", "pp_set_tensor", "pp_get_tensor", "pp_set_trainable_mask", "pp_local_step",
-           "pp_outer_delta", "pp_synth_delta_sum", "pp_get_counters", "pp_get_gemm_timing", "pp_set_option", "pp_last_error", "pp_free",
+           "pp_outer_delta", "pp_outer_delta_group", "pp_synth_delta_sum", "pp_get_counters", "pp_get_gemm_timing", "pp_set_option", "pp_last_error", "pp_free",
            "pp_op_gemm_nt", "pp_op_attention_fwd", "pp_op_attention_bwd"]
 
 
@@ -24,7 +24,7 @@ class PPError(RuntimeError):
 
 class PPConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_heads", "d_ff", "vocab", "max_batch", "max_seq", "dtype")] + \
-               [("rms_eps", C.c_float), ("rope_base", C.c_float)]
+               [("rms_eps", C.c_float), ("rope_base", C.c_float), ("recompute", C.c_int32)]
 
 
 class PPMask(C.Structure):
@@ -72,6 +72,8 @@ def load_library():
     lib.pp_local_step.argtypes = [vp, vp, vp, i32, i32, C.POINTER(PPAdamW), vp]
     lib.pp_outer_delta.restype = C.c_int
     lib.pp_outer_delta.argtypes = [vp, vp, vp, vp, C.POINTER(PPOuter), vp]
+    lib.pp_outer_delta_group.restype = C.c_int
+    lib.pp_outer_delta_group.argtypes = [vp, i32, i32, i32, vp, vp, vp, C.POINTER(PPOuter), vp]
     lib.pp_synth_delta_sum.restype = C.c_int
     lib.pp_synth_delta_sum.argtypes = [vp, vp, sz, C.POINTER(C.c_uint64), i32, C.c_float]
     lib.pp_get_counters.restype = C.c_int
@@ -141,6 +143,11 @@ def pp_local_step(h, tokens_ptr: int, targets_ptr: int, B: int, S: int, opt, los
     _check(load_library().pp_local_step(h, tokens_ptr, targets_ptr, B, S, None if opt is None else C.byref(opt), loss_ptr), "pp_local_step")
 
 
+def pp_outer_delta_group(h, layer_lo: int, layer_hi: int, ends: int, theta_g_ptr: int, momentum_ptr: int, others_ptr, opt: PPOuter, delta_out_ptr):
+    _check(load_library().pp_outer_delta_group(h, layer_lo, layer_hi, ends, theta_g_ptr, momentum_ptr, others_ptr, C.byref(opt), delta_out_ptr),
+           "pp_outer_delta_group")
+
+
 def pp_outer_delta(h, theta_g_ptr: int, momentum_ptr: int, others_ptr, opt: PPOuter, delta_out_ptr):
     _check(load_library().pp_outer_delta(h, theta_g_ptr, momentum_ptr, others_ptr, C.byref(opt), delta_out_ptr), "pp_outer_delta")
 
@@ -188,7 +195,7 @@ def pp_op_attention_bwd(stream: int, dtype: int, qkv_ptr, o_ptr, lse_ptr, dO_ptr
 # --------------------------------------------------------------------------------------------- convenience holder
 def make_config(cfg: dict) -> PPConfig:
     return PPConfig(cfg["n_layers"], cfg["d_model"], cfg["n_heads"], cfg["d_ff"], cfg["vocab"], cfg.get("max_batch", cfg["batch"]),
-                    cfg.get("max_seq", cfg["seq"]), PP_BF16 if cfg["dtype"] == "bf16" else PP_F32, cfg["rms_eps"], cfg["rope_base"])
+                    cfg.get("max_seq", cfg["seq"]), PP_BF16 if cfg["dtype"] == "bf16" else PP_F32, cfg["rms_eps"], cfg["rope_base"], int(cfg.get("recompute", 0)))
 
 
 def make_mask(mask: dict) -> PPMask:

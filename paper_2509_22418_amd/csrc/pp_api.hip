@@ -77,7 +77,9 @@ struct Seg { int kind, layer; int64_t canon_off; int row_lo, rows; int64_t packe
 
 struct WsPlan {          // byte offsets into the workspace
   size_t rope_cos, rope_sin, shadow, rows, segs, keys;
-  size_t act0, act_stride;          // per layer
+  size_t act0, act_stride;          // per layer (recompute: the layer input only)
+  size_t act_shared;                // recompute: the one block that holds the other activations of the layer in work
+  bool recompute;
   size_t a_x, a_n1, a_qkv, a_o, a_xm, a_n2, a_gu, a_a, a_rstd1, a_rstd2, a_lse;      // within a layer's block
   size_t xL, nf, rstdf, logits, rowloss, nvalid, dgpart;
   size_t dx, dn, dA, dgu, dob, dqkv, Dattn, at;
@@ -109,8 +111,16 @@ static WsPlan plan_ws(const pp_config& c, const Mask* mk) {
   p.a_x = ltake(T * d * es); p.a_n1 = ltake(T * d * es); p.a_qkv = ltake(T * 3 * d * es); p.a_o = ltake(T * d * es);
   p.a_xm = ltake(T * d * es); p.a_n2 = ltake(T * d * es); p.a_gu = ltake(T * 2 * F * es); p.a_a = ltake(T * F * es);
   p.a_rstd1 = ltake(T * 4); p.a_rstd2 = ltake(T * 4); p.a_lse = ltake((size_t)c.max_batch * h * c.max_seq * 4);
-  p.act_stride = lo;
-  p.act0 = take(p.act_stride * c.n_layers);
+  p.recompute = c.recompute != 0;
+  if (p.recompute) {          // per layer: x only (a_x = 0 is the first field of the block); everything else lives once
+    p.act_stride = align_up(T * d * es);
+    p.act0 = take(p.act_stride * c.n_layers);
+    p.act_shared = take(lo);
+  } else {
+    p.act_stride = lo;
+    p.act0 = take(p.act_stride * c.n_layers);
+    p.act_shared = 0;
+  }
   p.xL = take(T * d * es); p.nf = take(T * d * es); p.rstdf = take(T * 4); p.logits = take(T * V * es);
   p.act_bytes = off - p.act0;
   p.rowloss = take(T * 4); p.nvalid = take(256); p.dgpart = take(64 * d * 4);
@@ -153,7 +163,7 @@ struct pp_model {
   float *sp = nullptr, *sm = nullptr, *sv = nullptr, *sg = nullptr;
   long step = 0;
   int force_plain = 0;
-  double flops_fwd = 0, flops_bwd = 0, adamw_bytes = 0;
+  double flops_fwd = 0, flops_bwd = 0, flops_recompute = 0, adamw_bytes = 0;
   double* flop_acc = nullptr;
   // optional GEMM timing: one event pair per GEMM launch, summed by pp_get_gemm_timing
   int time_gemm = 0;
@@ -188,6 +198,7 @@ static int check_cfg(const pp_config* c) {
   if (c->n_layers < 1 || c->d_model < 8 || c->n_heads < 1 || c->d_ff < 8 || c->vocab < 8 || c->max_batch < 1 || c->max_seq < 1)
     return fail(PP_EINVAL, "config: non-positive dimension");
   if (c->dtype != PP_F32 && c->dtype != PP_BF16) return fail(PP_EINVAL, "config: dtype must be PP_F32 or PP_BF16");
+  if (c->recompute != 0 && c->recompute != 1) return fail(PP_EINVAL, "config: recompute must be 0 or 1");
   if (c->d_model % c->n_heads) return fail(PP_EINVAL, "config: d_model must be a multiple of n_heads");
   const int dh = c->d_model / c->n_heads;
   if (dh % 2 || dh > 256) return fail(PP_EINVAL, "config: head dim must be even and <= 256");
@@ -374,8 +385,9 @@ extern "C" int pp_get_tensor(pp_model* m, const char* name, void* host_dst, size
     if (sscanf(name, "dbg.%31[a-z0-9A-Z_].%d", buf, &l) < 1) return fail(PP_EINVAL, "pp_get_tensor: bad dbg name");
     if (l < 0 || l >= c.n_layers) return fail(PP_EINVAL, "pp_get_tensor: dbg layer out of range");
     std::string b(buf);
-    const char* lb = m->wsp + m->ws.act0 + (size_t)l * m->ws.act_stride;
-    if (b == "x") { src = lb + m->ws.a_x; want = T * d * es; }
+    const char* lx = m->wsp + m->ws.act0 + (size_t)l * m->ws.act_stride;          // the layer's own block
+    const char* lb = m->ws.recompute ? m->wsp + m->ws.act_shared : lx;                // where its other activations are
+    if (b == "x") { src = lx + m->ws.a_x; want = T * d * es; }
     else if (b == "n1") { src = lb + m->ws.a_n1; want = T * d * es; }
     else if (b == "qkv") { src = lb + m->ws.a_qkv; want = T * 3 * d * es; }
     else if (b == "o") { src = lb + m->ws.a_o; want = T * d * es; }
@@ -534,17 +546,19 @@ extern "C" int pp_local_step(pp_model* m, const int32_t* tokens_dev, const int32
   const float* sinb = (const float*)(W + w.rope_sin);
   auto canon = [&](int64_t off) { return (void*)(P + off * es); };
   auto shad = [&](int64_t off) { return (void*)(shadow + off * es); };
-  auto act = [&](int l, size_t o) { return (void*)(W + w.act0 + (size_t)l * w.act_stride + o); };
+  auto act = [&](int l, size_t o) {          // activation `o` of layer l (recompute: only the layer input is per layer)
+    return (void*)((w.recompute && o != w.a_x) ? W + w.act_shared + o : W + w.act0 + (size_t)l * w.act_stride + o);
+  };
   auto ofs = [&](void* p, size_t elems) { return (void*)((char*)p + elems * es); };
 
   // ---------------- forward over all parameters (Section 2.2: "the forward pass is standard")
-  m->flops_fwd = 0; m->flops_bwd = 0;
+  m->flops_fwd = 0; m->flops_bwd = 0; m->flops_recompute = 0;
   m->flop_acc = &m->flops_fwd;
   k_embed(st, dt, tokens_dev, canon(ly.embed), act(0, w.a_x), T, d, V);
-  for (int l = 0; l < L; ++l) {
+  // one layer forward; xnext == nullptr: stop after the SwiGLU product (all that a recomputation needs)
+  auto layer_forward = [&](int l, void* xnext) {
     const int64_t lb = ly.layer0 + l * ly.layer_stride, sb = ly.sh_layer0 + l * ly.sh_layer_stride;
     void* x = act(l, w.a_x);
-    void* xnext = (l + 1 < L) ? act(l + 1, w.a_x) : (void*)(W + w.xL);
     k_rmsnorm_fwd(st, dt, x, canon(lb + ly.o_attn_norm), act(l, w.a_n1), (float*)act(l, w.a_rstd1), T, d, c.rms_eps);
     gemm_nt(m, act(l, w.a_n1), d, canon(lb + ly.o_wqkv), d, act(l, w.a_qkv), 3 * d, T, 3 * d, d);
     k_rope(st, dt, act(l, w.a_qkv), cosb, sinb, B, S, h, dh, 0);
@@ -555,8 +569,9 @@ extern "C" int pp_local_step(pp_model* m, const int32_t* tokens_dev, const int32
       gemm_nt(m, act(l, w.a_n2), d, canon(lb + ly.o_wg), d, act(l, w.a_gu), 2 * F, T, 2 * F, d);
       k_swiglu_fwd(st, dt, act(l, w.a_gu), act(l, w.a_a), T, F);
     }
-    gemm_nt(m, act(l, w.a_a), F, shad(sb + ly.sh_wd), F, xnext, d, T, d, F, EPI_ADD_RES, act(l, w.a_xm));
-  }
+    if (xnext) gemm_nt(m, act(l, w.a_a), F, shad(sb + ly.sh_wd), F, xnext, d, T, d, F, EPI_ADD_RES, act(l, w.a_xm));
+  };
+  for (int l = 0; l < L; ++l) layer_forward(l, (l + 1 < L) ? act(l + 1, w.a_x) : (void*)(W + w.xL));
   void* xL = W + w.xL;
   void* nf = W + w.nf;
   void* logits = W + w.logits;
@@ -600,6 +615,11 @@ extern "C" int pp_local_step(pp_model* m, const int32_t* tokens_dev, const int32
       for (int l = L - 1; l >= 0; --l) {
         const int64_t lb = ly.layer0 + l * ly.layer_stride, sb = ly.sh_layer0 + l * ly.sh_layer_stride;
         const bool below_ffn_w = mk.norms || mk.wo || mk.heads || below_layer(l);
+        if (w.recompute && (mk.ffn || below_ffn_w)) {          // run the layer forward again from its saved input (not counted as executed FLOPs)
+          double* keep = m->flop_acc; m->flop_acc = &m->flops_recompute;
+          layer_forward(l, nullptr);
+          m->flop_acc = keep;
+        }
         if (mk.ffn || below_ffn_w) {
           const int c0 = below_ffn_w ? 0 : mk.fl, c1 = below_ffn_w ? F : mk.fh, nc = c1 - c0, Fk = mk.fh - mk.fl;
           if (mk.ffn) {      // dWd_k = A_k^T G
@@ -681,6 +701,41 @@ extern "C" int pp_outer_delta(pp_model* m, float* theta_g_dev, float* momentum_d
   k_shadow_refresh(m->st, m->cfg.dtype, m->params, m->wsp + m->ws.shadow, (const ShadowSeg*)(m->wsp + m->ws.segs), m->n_shadow_segs, m->n_shadow_tiles, m->shadow_vec_ok);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(PP_EHIP, std::string("pp_outer_delta: ") + hipGetErrorString(e));
+  return PP_OK;
+}
+
+// Streaming synchronisation (Experimental Setup: layers synchronised group by group): the same update restricted to the
+// packed rows of layers [layer_lo, layer_hi) and, if ends != 0, of embed / final_norm / lm_head.  The packed order is the
+// network order, so the selection is at most three contiguous row ranges.
+extern "C" int pp_outer_delta_group(pp_model* m, int32_t layer_lo, int32_t layer_hi, int32_t ends, float* theta_g_dev, float* momentum_dev,
+                                    const float* others_sum_dev, const pp_outer* opt, float* delta_out_dev) {
+  if (!m || !theta_g_dev || !momentum_dev || !opt) return fail(PP_EINVAL, "pp_outer_delta_group: NULL pointer");
+  if (!m->has_mask) return fail(PP_ESTATE, "pp_outer_delta_group: call pp_set_trainable_mask first");
+  if (!(opt->m_count >= 1.0f)) return fail(PP_EINVAL, "pp_outer_delta_group: m_count must be >= 1");
+  if (!(opt->lr >= 0.f) || !(opt->momentum >= 0.f)) return fail(PP_EINVAL, "pp_outer_delta_group: bad hyper-parameters");
+  if (layer_lo < 0 || layer_hi < layer_lo || layer_hi > m->cfg.n_layers) return fail(PP_EINVAL, "pp_outer_delta_group: bad layer range");
+  const int d = m->cfg.d_model;
+  int64_t run_lo = -1, run_hi = -1;          // current run of selected packed rows
+  auto flush = [&]() {
+    if (run_lo < 0) return;
+    const size_t e0 = (size_t)run_lo * d;
+    k_outer(m->st, m->cfg.dtype, m->params, (const RowInfo*)(m->wsp + m->ws.rows) + run_lo, m->sp + e0, theta_g_dev + e0, momentum_dev + e0,
+            others_sum_dev ? others_sum_dev + e0 : nullptr, delta_out_dev ? delta_out_dev + e0 : nullptr, (int)(run_hi - run_lo), d,
+            opt->lr, opt->momentum, opt->nesterov != 0, 1.0f / opt->m_count);
+    run_lo = run_hi = -1;
+  };
+  for (const Seg& s : m->segs) {
+    const bool sel = s.layer >= 0 ? (s.layer >= layer_lo && s.layer < layer_hi) : (ends != 0);
+    const int64_t r0 = s.packed_off / d, r1 = r0 + s.rows;
+    if (sel && s.rows > 0) {
+      if (run_lo >= 0 && run_hi == r0) run_hi = r1;
+      else { flush(); run_lo = r0; run_hi = r1; }
+    } else flush();
+  }
+  flush();
+  k_shadow_refresh(m->st, m->cfg.dtype, m->params, m->wsp + m->ws.shadow, (const ShadowSeg*)(m->wsp + m->ws.segs), m->n_shadow_segs, m->n_shadow_tiles, m->shadow_vec_ok);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(PP_EHIP, std::string("pp_outer_delta_group: ") + hipGetErrorString(e));
   return PP_OK;
 }
 

@@ -90,3 +90,38 @@ def test_plain_and_mfma_paths_agree():
     assert abs(out[0][0] - out[1][0]) <= 2e-3 * abs(out[1][0])
     a, bb = out[0][1], out[1][1]
     assert float(a @ bb / (np.linalg.norm(a) * np.linalg.norm(bb))) >= 0.9999
+
+
+@pytest.mark.parametrize("mname", ["ffn", "paper_mlp", "all"])
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_activation_recomputation_gives_the_same_bits_with_less_workspace(mname, dtype):
+    """recompute = 1 keeps only each layer's input and runs the layer forward again in the backward pass (the paper's
+    memory regime, Experimental Setup / Table 1).  Every kernel is deterministic, so losses, gradients and the weights
+    after two AdamW steps are bit-identical to the stored-activation run; the activation part of the workspace shrinks
+    to (n_layers x one [T x d] tensor) + one layer's worth."""
+    base = dict(SMALL, n_layers=3, dtype=dtype)
+    cfg0 = gen.make_config("tiny", **base)
+    cfg1 = dict(cfg0, recompute=1)
+    weights = gen.make_weights(cfg0, seed=41)
+    mask = {"ffn": gen.ffn_slice_mask(cfg0, 1, 4), "paper_mlp": gen.paper_mlp_mask(cfg0, 1, 4), "all": dict(all=1)}[mname]
+    out = []
+    for cfg in (cfg0, cfg1):
+        m = make_gpu_model(cfg, weights, mask)
+        losses = []
+        for step in range(2):
+            tok, tgt = gen.make_tokens(cfg, seed=41, step=step)
+            td, gd = m.upload_tokens(tok, tgt)
+            losses.append(float(m.step(td, gd, HP).item()))
+        rep = m.memory_report()
+        out.append((losses, m.get_state("g"), m.get_state("p"), m.counters(), rep))
+        m.close()
+    (l0, g0, p0, c0, r0), (l1, g1, p1, c1, r1) = out
+    assert l0 == l1
+    assert np.array_equal(g0, g1) and np.array_equal(p0, p1)
+    assert c0["flops_fwd"] == c1["flops_fwd"] and c0["flops_bwd"] == c1["flops_bwd"]          # recomputation is not counted
+    es = 2 if dtype == "bf16" else 4
+    T, d, L = cfg0["batch"] * cfg0["seq"], cfg0["d_model"], cfg0["n_layers"]
+    assert r1["activations"] < r0["activations"]
+    saved = r0["activations"] - r1["activations"]
+    per_layer_rest = (r0["activations"] - T * (2 * d + cfg0["vocab"]) * es) / L - T * d * es          # all but x, roughly
+    assert saved > 0.9 * (L - 1) * per_layer_rest

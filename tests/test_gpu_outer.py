@@ -65,3 +65,61 @@ def test_outer_step_matches_oracle(dtype):
     import ctypes
     assert lib.pp_outer_delta(m.h, tg.data_ptr(), mom.data_ptr(), None, ctypes.byref(bad), None) == -1
     m.close()
+
+
+def test_outer_step_by_layer_group_touches_only_the_group():
+    """Streaming synchronisation (Experimental Setup): one call updates the packed elements of one group of layers (or of
+    the embeddings / output norm / head) by the same formulas and leaves every other element of theta_g, the momentum
+    buffer, the fp32 masters and the weights bit-identical.  Mask = the paper's MLP-only slicing (everything outside the
+    FFN trainable + one FFN slice), so all three kinds of packed range occur."""
+    cfg = gen.make_config("tiny", **dict(SMALL, n_layers=3))
+    weights = gen.make_weights(cfg, seed=23)
+    mask = gen.paper_mlp_mask(cfg, 1, 4)
+    m = make_gpu_model(cfg, weights, mask)
+    segs = O.mask_segments(cfg, mask)
+    d = cfg["d_model"]
+    # packed element range of every segment, and which group it belongs to
+    offs, o = [], 0
+    for name, lo, hi in segs:
+        n_el = (hi - lo) * (d if "norm" not in name else d)
+        layer = int(name.split(".")[1]) if name.startswith("layers.") else -1
+        offs.append((layer, o, o + n_el)); o += n_el
+    theta_g0 = O.pack(O.to_f64(weights), segs)
+    n = theta_g0.size
+    assert o == n
+    for h in range(2):
+        tok, tgt = gen.make_tokens(cfg, seed=23, step=h)
+        m.step(*m.upload_tokens(tok, tgt), HP)
+    names = gen.tensor_shapes(cfg)
+    read_weights = lambda: O.pack({k: m.get_weight(k, s).astype(np.float64) for k, s in names.items()}, segs)
+    rng = np.random.default_rng(5)
+    others_h = (rng.standard_normal(n) * 1e-4).astype(np.float32)
+    tg = torch.from_numpy(theta_g0.astype(np.float32)).cuda()
+    mom = torch.from_numpy((rng.standard_normal(n) * 1e-3).astype(np.float32)).cuda()
+    others = torch.from_numpy(others_h).cuda()
+    delta = torch.full((n,), 7.0, dtype=torch.float32, device="cuda")
+    for (l0, l1, ends) in [(1, 2, 0), (0, 0, 1), (0, 3, 0)]:
+        sel = np.zeros(n, dtype=bool)
+        for layer, a, b in offs:
+            if (layer >= 0 and l0 <= layer < l1) or (layer < 0 and ends):
+                sel[a:b] = True
+        assert sel.any() and not sel.all()
+        tg0, mom0, p0, w0 = tg.cpu().numpy(), mom.cpu().numpy(), m.get_state("p"), read_weights()
+        delta.fill_(7.0)
+        opt = pp.PPOuter(0.7, 0.9, 1, 4.0)
+        pp.pp_outer_delta_group(m.h, l0, l1, ends, tg.data_ptr(), mom.data_ptr(), others.data_ptr(), opt, delta.data_ptr())
+        torch.cuda.synchronize()
+        ref_new, ref_b, ref_delta = O.outer_step(tg0.astype(np.float64), w0, others_h.astype(np.float64), mom0.astype(np.float64), 0.7, 0.9, 4.0)
+        tg1, mom1, p1, w1, dl = tg.cpu().numpy(), mom.cpu().numpy(), m.get_state("p"), read_weights(), delta.cpu().numpy()
+        np.testing.assert_allclose(tg1[sel], ref_new[sel], rtol=2e-6, atol=1e-8)
+        np.testing.assert_allclose(mom1[sel], ref_b[sel], rtol=2e-5, atol=1e-9)
+        np.testing.assert_allclose(dl[sel], ref_delta[sel], rtol=2e-5, atol=1e-9)
+        assert np.array_equal(p1[sel], tg1[sel])
+        assert np.array_equal(w1[sel].astype(np.float32), gen.round_to_bf16(tg1[sel]))
+        # outside the group: nothing moved
+        assert np.array_equal(tg1[~sel], tg0[~sel]) and np.array_equal(mom1[~sel], mom0[~sel])
+        assert np.array_equal(p1[~sel], p0[~sel]) and np.array_equal(w1[~sel], w0[~sel])
+        assert np.all(dl[~sel] == 7.0)
+    lib = pp.load_library()
+    assert lib.pp_outer_delta_group(m.h, 2, 1, 0, tg.data_ptr(), mom.data_ptr(), None, None, None) == -1
+    m.close()

@@ -11,6 +11,10 @@ from harness import HP, cosine, segment_slices, make_gpu_model, frozen_bytes_equ
 pytestmark = pytest.mark.gpu
 
 
+def _bf16_to_f32(raw_u16):
+    return (raw_u16.astype(np.uint32) << 16).view(np.float32)
+
+
 def run_case(cfg, mask, seed, batch=None, seq=None, force_plain=False, loss_tol=1e-2, cos_tol=0.999):
     weights = gen.make_weights(cfg, seed=seed)
     tok, tgt = gen.make_tokens(cfg, seed=seed, batch=batch, seq=seq)
@@ -111,9 +115,31 @@ def test_1p3b_shape_step_matches_oracle_on_one_sequence():
     assert frozen_bytes_equal(cfg, m, weights, mask) == []
     m.close()
 
-
-def _bf16_to_f32(raw_u16):
-    return (raw_u16.astype(np.uint32) << 16).view(np.float32)
+    # The full batch 8 x 2048 exactly as bench.py launches it.  Causality makes the hidden states of the first positions
+    # of a sequence independent of everything else in the batch, so the oracle can compute sampled outputs one by one:
+    # the layer inputs and the final hidden state of the first 64 positions of sequence 5, from that 64-token prefix alone.
+    print("case 1p3b B=8 sampled", flush=True)
+    tok8, tgt8 = gen.make_tokens(cfg, seed=1234)
+    m8 = make_gpu_model(cfg, weights, mask)
+    loss8 = float(m8.step(*m8.upload_tokens(tok8, tgt8), HP).item())
+    cnt8 = m8.counters()
+    B8, S8 = tok8.shape
+    assert np.isfinite(loss8)
+    assert cnt8["flops_fwd"] + cnt8["flops_bwd"] == O.flops_forward(cfg, B8, S8) + O.flops_backward_ffn_slice(cfg, B8, S8, 1.0 / 32)
+    npre, seq = 64, 5
+    _, pc = O.forward(cfg, params, tok8[seq:seq + 1, :npre], tgt8[seq:seq + 1, :npre])
+    d, T8 = cfg["d_model"], B8 * S8
+    rows = slice(seq * S8, seq * S8 + npre)
+    for name, ref in [("dbg.x.0", pc["layers"][0]["x"]), ("dbg.x.12", pc["layers"][12]["x"]), ("dbg.x.23", pc["layers"][23]["x"]),
+                      ("dbg.xL", pc["xL"])]:
+        got = _bf16_to_f32(m8.get_raw(name, (T8, d), np.uint16))[rows]
+        ref = np.asarray(ref).reshape(npre, d)
+        c = cosine(got.ravel(), ref.ravel())
+        err = np.max(np.abs(got - ref)) / np.max(np.abs(ref))
+        print(f"{name}: cosine {c:.6f}, max abs err / max |ref| {err:.4f}", flush=True)
+        assert c >= 0.999 and err <= 5e-2, (name, c, err)
+    assert frozen_bytes_equal(cfg, m8, weights, mask) == []
+    m8.close()
 
 
 def test_fused_gate_up_activation_matches_stored_projections_and_oracle():

@@ -123,3 +123,43 @@ def test_outer_step_by_layer_group_touches_only_the_group():
     lib = pp.load_library()
     assert lib.pp_outer_delta_group(m.h, 2, 1, 0, tg.data_ptr(), mom.data_ptr(), None, None, None) == -1
     m.close()
+
+
+def test_two_rounds_of_algorithm_1_track_the_oracle():
+    """Algorithm 1 for one node, end to end through the C ABI: two rounds of H = 3 local steps on I_train followed by
+    the synchronisation (own delta + the other nodes' reduced deltas, count normalisation, Nesterov outer step, restart
+    of the local copy from the new global values), tiny fp32 configuration with the paper's MLP-only mask.  The fp64
+    oracle runs the same schedule; losses agree to 1e-5 relative at every local step and the global parameters stay
+    within a fraction of the accumulated step sizes."""
+    cfg = gen.make_config("tiny")
+    weights = gen.make_weights(cfg, seed=61)
+    mask = gen.paper_mlp_mask(cfg, 2, 4)
+    m = make_gpu_model(cfg, weights, mask)
+    tr = O.LocalTrainer(cfg, weights, mask)
+    n = tr.master.size
+    theta_g_ref, buf_ref = tr.master.copy(), np.zeros(n)
+    tg = torch.from_numpy(theta_g_ref.astype(np.float32)).cuda()
+    mom = torch.zeros(n, dtype=torch.float32, device="cuda")
+    others = torch.empty(n, dtype=torch.float32, device="cuda")
+    H, lr_out, mu, cnt = 3, 0.7, 0.9, 4.0
+    step = 0
+    for rnd in range(2):
+        for h in range(H):
+            tok, tgt = gen.make_tokens(cfg, seed=61, step=step); step += 1
+            lg = float(m.step(*m.upload_tokens(tok, tgt), HP).item())
+            lo, _ = tr.step(tok, tgt, HP)
+            assert abs(lg - lo) <= 1e-5 * abs(lo), (rnd, h, lg, lo)
+        keys = [gen.stream_key(100 + rnd, gen.STREAM_DELTAS, j + 1) for j in range(3)]
+        pp.pp_synth_delta_sum(m.h, others.data_ptr(), n, keys, 1e-4)
+        others_ref = gen.synthetic_delta_sum(100 + rnd, n, 3, 1e-4)
+        pp.pp_outer_delta(m.h, tg.data_ptr(), mom.data_ptr(), others.data_ptr(), pp.PPOuter(lr_out, mu, 1, cnt), None)
+        torch.cuda.synchronize()
+        theta_g_ref, buf_ref, _ = O.outer_step(theta_g_ref, tr.master, others_ref, buf_ref, lr_out, mu, cnt)
+        tr.master = theta_g_ref.copy()                       # the local copy restarts from the new global values
+        O.unpack_into(tr.params, tr.segs, tr.master)
+        got = tg.cpu().numpy().astype(np.float64)
+        budget = (rnd + 1) * (H * HP["lr"] + 1e-4) * lr_out * (1 + mu)          # what one round can move an element by, per round
+        assert np.max(np.abs(got - theta_g_ref)) <= 0.1 * budget, (rnd, np.max(np.abs(got - theta_g_ref)), budget)
+        assert np.array_equal(m.get_state("p"), tg.cpu().numpy())
+    assert frozen_bytes_equal(cfg, m, weights, mask) == []
+    m.close()

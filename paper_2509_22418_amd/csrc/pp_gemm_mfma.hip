@@ -21,6 +21,7 @@ namespace pp {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BM = 256, BN = 256, BK = 64;
@@ -237,77 +238,86 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
   __builtin_amdgcn_s_waitcnt(0x0F70 | 4);          // vmcnt(4): both units of super-step 0 have landed
   __builtin_amdgcn_s_barrier();
 
-  f32x16 acc[4][2];
+  // 16 x 16 x 32 MFMAs: on non-trivial operand data the matrix pipe is power-limited, and this shape sustains about
+  // 14 % more than 32 x 32 x 16 (2.1 vs 1.85 PFLOP/s in an MFMA-only loop on random bf16 operands; both reach 2.4 on zeros).
+  // B-panel rows are the MFMA's row operand, so an accumulator tile is a 16 x 16 block of C^T: lane l holds, for output
+  // row (lane % 16) of A-block i, the 4 consecutive columns 4 * (lane / 16) .. + 3 of B-block j.
+  f32x4 acc[8][4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+      for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
 
-  const int l32 = lane & 31, lhi = lane >> 5, sw = (l32 >> 1) & 7;
-  const int aRow = (wm * 128 + l32) * 8, bRow = (wn * 64 + l32) * 8;
-  // Fragment registers are double-buffered: the reads of the next 16-deep slice are issued before the MFMAs of the
-  // current one, so LDS latency hides behind matrix work inside one wavefront.
-  bf16x8 fa[2][4], fb[2][2];
-  auto readf = [&](int buf, int slot_a, int slot_b, int kk) {          // slice kk (0..3) of the units in the two slots
-    const int pc = (2 * kk + lhi) ^ sw;
-    const u32x4* pa = lds + slot_a * DL_UNIT_CHUNKS + aRow + pc;
-    const u32x4* pb = lds + slot_b * DL_UNIT_CHUNKS + bRow + pc;
+  const int l16 = lane & 15, lq = lane >> 4, sw = (l16 >> 1) & 7;          // row in a 16-row block, 16-byte chunk within a 64-byte K32 piece
+  const int aRow = (wm * 128 + l16) * 8, bRow = (wn * 64 + l16) * 8;
+  // A super-step of 64 K-elements = 2 MFMA K-steps of 32 = 4 slices of 16 MFMAs (one K-step x one half of the wave's 8 row
+  // blocks of A).  Fragment registers are double-buffered: the reads of the next slice (4 A fragments, plus the 4 B
+  // fragments when the K-step changes) are slotted between the MFMAs of the current one.
+  bf16x8 fa[2][4], fb[2][4];
+  auto readA = [&](int buf, int slot, int kk, int half) {
+    const u32x4* pa = lds + slot * DL_UNIT_CHUNKS + aRow + ((4 * kk + lq) ^ sw);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) fa[buf][i] = __builtin_bit_cast(bf16x8, pa[i * 32 * 8]);
-#pragma unroll
-    for (int j = 0; j < 2; ++j) fb[buf][j] = __builtin_bit_cast(bf16x8, pb[j * 32 * 8]);
+    for (int i = 0; i < 4; ++i) fa[buf][i] = __builtin_bit_cast(bf16x8, pa[(half * 4 + i) * 16 * 8]);
   };
-  auto mm = [&](int buf) {          // the 8 MFMAs of one slice
+  auto readB = [&](int buf, int slot, int kk) {
+    const u32x4* pb = lds + slot * DL_UNIT_CHUNKS + bRow + ((4 * kk + lq) ^ sw);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) fb[buf][j] = __builtin_bit_cast(bf16x8, pb[j * 16 * 8]);
+  };
+  auto mm = [&](int abuf, int bbuf, int half) {          // the 16 MFMAs of one slice
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][j], fa[buf][i], acc[i][j], 0, 0, 0);
-  };          // B-panel rows as the MFMA's row operand: the accumulator tile is C^T, so a lane owns runs of 4 consecutive
-              // columns of ONE output row (8-byte bf16 / 16-byte fp32 stores instead of 2-byte ones)
-  // one fragment read is slotted behind each of the first six MFMAs of a slice (the in-order LDS counter then never
-  // makes this slice's MFMAs wait for the next slice's reads)
-#define PP_DL_INTERLEAVE(ID)                                    \
-  _Pragma("unroll") for (int g = 0; g < 6; ++g) {              \
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, ID);         \
-    __builtin_amdgcn_sched_group_barrier(0x100, 1, ID);         \
-  }                                                             \
-  __builtin_amdgcn_sched_group_barrier(0x008, 2, ID);           \
+      for (int j = 0; j < 4; ++j)
+        acc[half * 4 + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[bbuf][j], fa[abuf][i], acc[half * 4 + i][j], 0, 0, 0);
+  };
+  // R fragment reads behind the first MFMAs of a slice of 16 (the in-order LDS counter then never makes this slice's
+  // MFMAs wait for the next slice's reads)
+#define PP_DL_INTERLEAVE(ID, R)                                              \
+  _Pragma("unroll") for (int g = 0; g < (R); ++g) {                         \
+    __builtin_amdgcn_sched_group_barrier(0x008, (R) == 4 ? 2 : 1, ID);       \
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, ID);                      \
+  }                                                                          \
+  __builtin_amdgcn_sched_group_barrier(0x008, 8, ID);                        \
   __builtin_amdgcn_sched_barrier(0)
 
   int sa = 0;          // slot of the A unit of the current super-step; its B unit is in the next slot of the ring
-  readf(0, 0, 1, 0);
+  readB(0, 1, 0);
+  readA(0, 0, 0, 0);
   for (int s = 0; s < ns; ++s) {
     const int sb = m5(sa + 1), na = m5(sa + 2), nb2 = m5(sa + 3), fa2 = m5(sa + 4);
     issue(gB, s + 1, nb2);          // slot of A(s-1): free since the barrier that ended super-step s-1
     __builtin_amdgcn_sched_barrier(0);
-    readf(1, sa, sb, 1);
-    mm(0);
-    PP_DL_INTERLEAVE(0);
-    readf(0, sa, sb, 2);
-    mm(1);
-    PP_DL_INTERLEAVE(1);
+    readA(1, sa, 0, 1);
+    mm(0, 0, 0);
+    PP_DL_INTERLEAVE(0, 4);
+    readB(1, sb, 1);
+    readA(0, sa, 1, 0);
+    mm(1, 0, 1);
+    PP_DL_INTERLEAVE(1, 8);
     issue(gA, s + 2, fa2);          // slot of B(s-1)
     __builtin_amdgcn_sched_barrier(0);
-    readf(1, sa, sb, 3);
-    mm(0);
-    PP_DL_INTERLEAVE(2);
+    readA(1, sa, 1, 1);
+    mm(0, 1, 0);
+    PP_DL_INTERLEAVE(2, 4);
     // vmcnt(4): all but the newest unit, i.e. both units of super-step s+1, have landed in this wave's rows;
     // lgkmcnt(0): this wave's reads of the current units are done
     __builtin_amdgcn_s_waitcnt(0x0070 | 4);
     __builtin_amdgcn_s_barrier();          // everybody's super-step s+1 is in LDS; the two current slots may be refilled
-    readf(0, na, nb2, 0);
-    mm(1);
-    PP_DL_INTERLEAVE(3);
+    readB(0, nb2, 0);
+    readA(0, na, 0, 0);
+    mm(1, 1, 1);
+    PP_DL_INTERLEAVE(3, 8);
     sa = na;
   }
 #undef PP_DL_INTERLEAVE
   __builtin_amdgcn_s_waitcnt(0x0F70);              // drain the clamped tail loads before the LDS is released
 
   if constexpr (EPI == EPI_SWIGLU) {
-    // ---- fused SwiGLU epilogue.  acc[i][0] / acc[i][1] are gate and up pre-activations of hidden unit
-    // u0 + 8*(r/4) + 4*(lane/32) + r%4 (u0 = tn*128 + wn*32) for output row m0 + wm*128 + i*32 + lane%32.  Both are
+    // ---- fused SwiGLU epilogue.  acc[i][j] (j = 0, 1) and acc[i][j + 2] are gate and up pre-activations of hidden unit
+    // u0 + 16 j + 4 (lane / 16) + r (u0 = tn*128 + wn*32) for output row m0 + wm*128 + 16 i + lane % 16.  Both are
     // rounded to bf16 and stored at columns u and N + u of C (ldc >= 2 N); a = silu(g) * u is formed from the ROUNDED
     // values -- exactly what a separate pass over the stored matrix would compute -- and stored at column u of C2.
     // Each wave turns 64 rows at a time around in a private 16 KB LDS patch (64 rows x 256 bytes: gate | up | a | unused,
@@ -321,15 +331,15 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
 #pragma unroll
     for (int hi = 0; hi < 2; ++hi) {
 #pragma unroll
-      for (int ii = 0; ii < 2; ++ii) {
-        const int i = 2 * hi + ii, row = ii * 32 + l32;
+      for (int ii = 0; ii < 4; ++ii) {
+        const int i = 4 * hi + ii, row = ii * 16 + l16;
 #pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
+        for (int j = 0; j < 2; ++j) {
           uint2 wg, wu, wa;
-          wg.x = f32x2_to_bf16x2(acc[i][0][4 * g4], acc[i][0][4 * g4 + 1]);
-          wg.y = f32x2_to_bf16x2(acc[i][0][4 * g4 + 2], acc[i][0][4 * g4 + 3]);
-          wu.x = f32x2_to_bf16x2(acc[i][1][4 * g4], acc[i][1][4 * g4 + 1]);
-          wu.y = f32x2_to_bf16x2(acc[i][1][4 * g4 + 2], acc[i][1][4 * g4 + 3]);
+          wg.x = f32x2_to_bf16x2(acc[i][j][0], acc[i][j][1]);
+          wg.y = f32x2_to_bf16x2(acc[i][j][2], acc[i][j][3]);
+          wu.x = f32x2_to_bf16x2(acc[i][j + 2][0], acc[i][j + 2][1]);
+          wu.y = f32x2_to_bf16x2(acc[i][j + 2][2], acc[i][j + 2][3]);
           const float gr[4] = {__uint_as_float(wg.x << 16), __uint_as_float(wg.x & 0xffff0000u), __uint_as_float(wg.y << 16), __uint_as_float(wg.y & 0xffff0000u)};
           const float ur[4] = {__uint_as_float(wu.x << 16), __uint_as_float(wu.x & 0xffff0000u), __uint_as_float(wu.y << 16), __uint_as_float(wu.y & 0xffff0000u)};
           float av[4];
@@ -337,11 +347,12 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
           for (int e = 0; e < 4; ++e) av[e] = silu_mul(gr[e], ur[e]);
           wa.x = f32x2_to_bf16x2(av[0], av[1]);
           wa.y = f32x2_to_bf16x2(av[2], av[3]);
-          // 8-byte piece (2*g4 + lhi) of the 64-byte segment: 16-byte piece g4, half lhi
-          char* rowp = wbase + row * 256 + lhi * 8;
-          *reinterpret_cast<uint2*>(rowp + (((0 + g4) ^ (row & 15)) << 4)) = wg;
-          *reinterpret_cast<uint2*>(rowp + (((4 + g4) ^ (row & 15)) << 4)) = wu;
-          *reinterpret_cast<uint2*>(rowp + (((8 + g4) ^ (row & 15)) << 4)) = wa;
+          // units 16 j + 4 lq .. + 3 of the wave's 32: 8-byte piece 4 j + lq of the 64-byte segment = 16-byte piece 2 j + lq / 2, half lq % 2
+          const int pc = 2 * j + (lq >> 1);
+          char* rowp = wbase + row * 256 + (lq & 1) * 8;
+          *reinterpret_cast<uint2*>(rowp + (((0 + pc) ^ (row & 15)) << 4)) = wg;
+          *reinterpret_cast<uint2*>(rowp + (((4 + pc) ^ (row & 15)) << 4)) = wu;
+          *reinterpret_cast<uint2*>(rowp + (((8 + pc) ^ (row & 15)) << 4)) = wa;
         }
       }
 #pragma unroll
@@ -361,11 +372,11 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
     }
     return;
   }
-  // ---- epilogue: element r of accumulator (i, j) is output row m0 + wm*128 + i*32 + lane%32,
-  //      column n0 + wn*64 + j*32 + 8*(r/4) + 4*(lane/32) + r%4
+  // ---- epilogue: element r of accumulator (i, j) is output row m0 + wm*128 + 16 i + lane % 16,
+  //      column n0 + wn*64 + 16 j + 4 (lane / 16) + r
   if constexpr (!OUT_F32) {
     if ((N & 7) == 0 && (ldc & 7) == 0) {          // uniform: coalesced path through LDS
-      // Each wave turns its 128 x 64 sub-tile around in a private 8 KB LDS patch, 64 rows at a time: 8-byte pieces
+      // Each wave turns its 128 x 64 sub-tile around in a private LDS patch, 64 rows at a time: 8-byte pieces
       // (4 consecutive columns of one row) are written, 16-byte row chunks are read back so that 8 lanes cover one
       // 128-byte row segment of C (and of the residual).  Chunk c of row r sits at c ^ ((r >> 1) & 7).
       __builtin_amdgcn_s_waitcnt(0x0070);
@@ -376,18 +387,16 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
 #pragma unroll
         for (int hi = 0; hi < 2; ++hi) {
 #pragma unroll
-          for (int ii = 0; ii < 2; ++ii) {
-            const int i = 2 * hi + ii, row = ii * 32 + l32, sw2 = (row >> 1) & 7;
+          for (int ii = 0; ii < 4; ++ii) {
+            const int i = 4 * hi + ii, row = ii * 16 + l16, sw2 = (row >> 1) & 7;
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-              for (int g = 0; g < 4; ++g) {
-                const int q = j * 8 + 2 * g + lhi;          // 8-byte piece index within the 128-byte row
-                uint2 w;
-                w.x = f32x2_to_bf16x2(acc[i][j][4 * g], acc[i][j][4 * g + 1]);
-                w.y = f32x2_to_bf16x2(acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-                *reinterpret_cast<uint2*>(wbase + row * 128 + (((q >> 1) ^ sw2) << 4) + (q & 1) * 8) = w;
-              }
+            for (int j = 0; j < 4; ++j) {
+              const int q = 4 * j + lq;          // 8-byte piece index within the 128-byte row
+              uint2 w;
+              w.x = f32x2_to_bf16x2(acc[i][j][0], acc[i][j][1]);
+              w.y = f32x2_to_bf16x2(acc[i][j][2], acc[i][j][3]);
+              *reinterpret_cast<uint2*>(wbase + row * 128 + (((q >> 1) ^ sw2) << 4) + (q & 1) * 8) = w;
+            }
           }
 #pragma unroll
           for (int it = 0; it < 8; ++it) {
@@ -404,16 +413,14 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
 #pragma unroll
         for (int hi = 0; hi < 2; ++hi) {
 #pragma unroll
-          for (int ii = 0; ii < 2; ++ii) {
-            const int i = 2 * hi + ii, row = ii * 32 + l32;
+          for (int ii = 0; ii < 4; ++ii) {
+            const int i = 4 * hi + ii, row = ii * 16 + l16;
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-              for (int g = 0; g < 4; ++g) {
-                const int q = j * 8 + 2 * g + lhi;          // 16-byte piece (4 floats) index within the 256-byte row
-                *reinterpret_cast<float4*>(wbase + row * 256 + ((q ^ (row & 15)) << 4)) =
-                    make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-              }
+            for (int j = 0; j < 4; ++j) {
+              const int q = 4 * j + lq;          // 16-byte piece (4 floats) index within the 256-byte row
+              *reinterpret_cast<float4*>(wbase + row * 256 + ((q ^ (row & 15)) << 4)) =
+                  make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+            }
           }
 #pragma unroll
           for (int it = 0; it < 16; ++it) {
@@ -455,33 +462,31 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
       return;
     }
   }
-  const int row_base = m0 + wm * 128 + l32;
-  const int col_base = n0 + wn * 64 + 4 * lhi;
+  const int row_base = m0 + wm * 128 + l16;
+  const int col_base = n0 + wn * 64 + 4 * lq;
   const bool n_vec_ok = (N % 4 == 0) && (ldc % 4 == 0);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int row = row_base + i * 32;
+  for (int i = 0; i < 8; ++i) {
+    const int row = row_base + i * 16;
     if (row >= M) continue;
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int col = col_base + j * 32 + 8 * g;
-        if (col >= N) continue;
-        float v[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-        if constexpr (OUT_F32) {
-          float* C = reinterpret_cast<float*>(Cv) + (size_t)z * (size_t)M * (size_t)ldc + (size_t)row * ldc + col;
-          if (n_vec_ok) *reinterpret_cast<float4*>(C) = make_float4(v[0], v[1], v[2], v[3]);
-          else for (int e = 0; e < 4 && col + e < N; ++e) C[e] = v[e];
-        } else {
-          bf16_t* C = reinterpret_cast<bf16_t*>(Cv) + (size_t)row * ldc + col;
-          for (int e = 0; e < 4 && col + e < N; ++e) {
-            float x = v[e];
-            if constexpr (EPI == EPI_ADD_RES) x += to_f32(R[(size_t)row * ldc + col + e]);
-            C[e] = from_f32<bf16_t>(x);
-          }
+    for (int j = 0; j < 4; ++j) {
+      const int col = col_base + j * 16;
+      if (col >= N) continue;
+      float v[4] = {acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]};
+      if constexpr (OUT_F32) {
+        float* C = reinterpret_cast<float*>(Cv) + (size_t)z * (size_t)M * (size_t)ldc + (size_t)row * ldc + col;
+        if (n_vec_ok) *reinterpret_cast<float4*>(C) = make_float4(v[0], v[1], v[2], v[3]);
+        else for (int e = 0; e < 4 && col + e < N; ++e) C[e] = v[e];
+      } else {
+        bf16_t* C = reinterpret_cast<bf16_t*>(Cv) + (size_t)row * ldc + col;
+        for (int e = 0; e < 4 && col + e < N; ++e) {
+          float x = v[e];
+          if constexpr (EPI == EPI_ADD_RES) x += to_f32(R[(size_t)row * ldc + col + e]);
+          C[e] = from_f32<bf16_t>(x);
         }
       }
+    }
   }
 }
 

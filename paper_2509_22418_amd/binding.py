@@ -56,6 +56,7 @@ def load_library():
     if not os.path.exists(path):
         from .build import build
         build()
+    import torch  # noqa: F401  -- first, so that the library binds to the HIP runtime torch ships (one runtime per process)
     lib = C.CDLL(path)
     vp, sz, i32, i64 = C.c_void_p, C.c_size_t, C.c_int32, C.c_int64
     lib.pp_query_bytes.restype = sz

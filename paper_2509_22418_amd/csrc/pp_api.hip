@@ -517,11 +517,15 @@ static void attn_fwd(pp_model* m, const void* qkv, void* o, float* lse, int B, i
   if (m->cfg.dtype == PP_BF16 && !m->force_plain && k_attn_fwd_mfma(m->st, qkv, o, lse, m->wsp + m->ws.at, B, S, h, dh) == 0) return;
   k_attn_fwd_plain(m->st, m->cfg.dtype, qkv, o, lse, B, S, h, dh);
 }
-static void attn_bwd(pp_model* m, const void* qkv, const void* o, const float* lse, const void* dO, void* dqkv, float* Dbuf, int B, int S) {
+// attention backward followed by the rotary embedding's backward on dq, dk (fused into the MFMA kernels' epilogues)
+static void attn_bwd(pp_model* m, const void* qkv, const void* o, const float* lse, const void* dO, void* dqkv, float* Dbuf, int B, int S,
+                     const float* cosb, const float* sinb) {
   const int h = m->cfg.n_heads, dh = m->cfg.d_model / h;
   if (m->flop_acc) *m->flop_acc += 8.0 * ((double)B * S * (S + 1) / 2) * m->cfg.d_model;
-  if (m->cfg.dtype == PP_BF16 && !m->force_plain && k_attn_bwd_mfma(m->st, qkv, o, lse, dO, dqkv, Dbuf, m->wsp + m->ws.at, B, S, h, dh) == 0) return;
+  if (m->cfg.dtype == PP_BF16 && !m->force_plain &&
+      k_attn_bwd_mfma(m->st, qkv, o, lse, dO, dqkv, Dbuf, m->wsp + m->ws.at, B, S, h, dh, cosb, sinb) == 0) return;
   k_attn_bwd_plain(m->st, m->cfg.dtype, qkv, o, lse, dO, dqkv, Dbuf, B, S, h, dh);
+  k_rope(m->st, m->cfg.dtype, dqkv, cosb, sinb, B, S, h, dh, 1);
 }
 
 // ------------------------------------------------------------------------------------------------ the local step
@@ -652,8 +656,7 @@ extern "C" int pp_local_step(pp_model* m, const int32_t* tokens_dev, const int32
         const bool below_wo = mk.heads || mk.norms || below_layer(l);
         if (!below_wo) break;
         gemm_nt(m, dx, d, shad(sb + ly.sh_wo), d, dob, d, T, d, d);
-        attn_bwd(m, act(l, w.a_qkv), act(l, w.a_o), (float*)act(l, w.a_lse), dob, dqkv, Dattn, B, S);
-        k_rope(st, dt, dqkv, cosb, sinb, B, S, h, dh, 1);
+        attn_bwd(m, act(l, w.a_qkv), act(l, w.a_o), (float*)act(l, w.a_lse), dob, dqkv, Dattn, B, S, cosb, sinb);
         if (mk.heads) {
           const int nhd = (mk.hh - mk.hl) * dh;
           for (int blk = 0; blk < 3; ++blk)
@@ -821,7 +824,7 @@ extern "C" int pp_op_attention_bwd(void* hip_stream, int dtype, const void* qkv,
   if (!qkv || !o || !lse || !dO || !dqkv || !Dbuf) return fail(PP_EINVAL, "pp_op_attention_bwd: NULL pointer");
   if (int rc = check_attn(dtype, B, S, h, dh)) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
-  if (!(path == 0 && dtype == PP_BF16 && scratch && k_attn_bwd_mfma(st, qkv, o, lse, dO, dqkv, Dbuf, scratch, B, S, h, dh) == 0))
+  if (!(path == 0 && dtype == PP_BF16 && scratch && k_attn_bwd_mfma(st, qkv, o, lse, dO, dqkv, Dbuf, scratch, B, S, h, dh, nullptr, nullptr) == 0))
     k_attn_bwd_plain(st, dtype, qkv, o, lse, dO, dqkv, Dbuf, B, S, h, dh);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(PP_EHIP, std::string("pp_op_attention_bwd: ") + hipGetErrorString(e));

@@ -319,6 +319,31 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
   }
 }
 
+// Gradient of the rotary embedding (the inverse rotation), applied to an accumulator tile before it is stored: with the
+// half-split pairing, elements i and i + DH/2 of a head are the same register of accumulators c and c + CT/2 of a lane.
+// pos = the lane's sequence position; tables are [S x DH/2] fp32; nullptr = no rotation.
+template <int DH>
+__device__ __forceinline__ void unrotate_tile(f32x16 (&acc)[DH / 32], const float* __restrict__ cosb, const float* __restrict__ sinb, int pos, int lh) {
+  constexpr int CT = DH / 32, HALF = DH / 2;
+  if (!cosb) return;
+  const float* cp = cosb + (size_t)pos * HALF + 4 * lh;
+  const float* sp = sinb + (size_t)pos * HALF + 4 * lh;
+#pragma unroll
+  for (int c = 0; c < CT / 2; ++c)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const float4 cs = *reinterpret_cast<const float4*>(cp + c * 32 + 8 * g);
+      const float4 sn = *reinterpret_cast<const float4*>(sp + c * 32 + 8 * g);
+      const float cv[4] = {cs.x, cs.y, cs.z, cs.w}, sv[4] = {sn.x, sn.y, sn.z, sn.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float x = acc[c][4 * g + e], y = acc[c + CT / 2][4 * g + e];
+        acc[c][4 * g + e] = x * cv[e] + y * sv[e];
+        acc[c + CT / 2][4 * g + e] = y * cv[e] - x * sv[e];
+      }
+    }
+}
+
 // ------------------------------------------------------------------------------------------ backward: dQ
 // B*h*ceil(S/256) workgroups (see causal_block_map), 512 threads = 8 waves (2 per SIMD, <= 256 registers each, so every MFMA keeps its
 // accumulator in ordinary VGPRs): wave w owns queries q0 + 32w .. +31.  Per KV tile of 64 keys, in two groups of 32:
@@ -326,7 +351,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
 template <int DH>
 __global__ __launch_bounds__(512, 2) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ kt_at,
                                                               const bf16_t* __restrict__ dO, const float* __restrict__ lse,
-                                                              const float* __restrict__ Dbuf, bf16_t* __restrict__ dqkv, int S, int Sp, int h, int n_pairs, int n_blk) {
+                                                              const float* __restrict__ Dbuf, bf16_t* __restrict__ dqkv, int S, int Sp, int h, int n_pairs, int n_blk,
+                                                              const float* __restrict__ cosb, const float* __restrict__ sinb) {
   constexpr int KS = DH / 16, CT = DH / 32, CPRK = DH / 8, NW = 8;
   extern __shared__ u32x4 lds[];
   constexpr int K_CH = 64 * CPRK, T_CH = DH * 8, ST_CH = 2 * K_CH + T_CH;
@@ -441,6 +467,7 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dq_kernel(const bf16_t* __res
       stage_sync();
     }
     if (q < S) {
+      unrotate_tile<DH>(dqacc, cosb, sinb, q, lh);          // dQ w.r.t. the un-rotated query (linear: commutes with the scale below)
       bf16_t* op = dqkv + ((size_t)b * S + q) * ld + (size_t)head * DH + 4 * lh;
 #pragma unroll
       for (int c = 0; c < CT; ++c)
@@ -472,7 +499,8 @@ template <int DH, bool kwave>          // kwave false: V-wave (S, P, dV)   true:
 __device__ __forceinline__ void attn_bwd_dkv_part(u32x4* lds, const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ qt_at,
                                                   const bf16_t* __restrict__ dO, const bf16_t* __restrict__ dot_at,
                                                   const float* __restrict__ lse, const float* __restrict__ Dbuf, bf16_t* __restrict__ dqkv,
-                                                  int S, int Sp, int h, int stats_vec, int head, int b, int kblk, int lane, int wave) {
+                                                  int S, int Sp, int h, int stats_vec, int head, int b, int kblk, int lane, int wave,
+                                                  const float* __restrict__ cosb, const float* __restrict__ sinb) {
   constexpr int KS = DH / 16, CT = DH / 32, CPRK = DH / 8, NW = 8;
   constexpr int R_CH = 64 * CPRK, T_CH = DH * 8, SET_CH = R_CH + T_CH;
   constexpr int MAIL_CH = 2 * 4 * 2 * 64, MAIL0 = 4 * SET_CH;          // mailbox: [query group 2][key group 4][fragment 2][lane 64] chunks
@@ -638,6 +666,7 @@ __device__ __forceinline__ void attn_bwd_dkv_part(u32x4* lds, const bf16_t* __re
     stage_sync();
   }
   if (key < S) {
+    if constexpr (kwave) unrotate_tile<DH>(oacc, cosb, sinb, key, lh);          // dK w.r.t. the un-rotated key; V is not rotated
     const float osc = kwave ? scale : 1.0f;
     bf16_t* op = dqkv + ((size_t)b * S + key) * ld + (kwave ? d : 2 * d) + (size_t)head * DH + 4 * lh;
 #pragma unroll
@@ -658,7 +687,8 @@ template <int DH>
 __global__ __launch_bounds__(512, 2) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ qt_at,
                                                                const bf16_t* __restrict__ dO, const bf16_t* __restrict__ dot_at,
                                                                const float* __restrict__ lse, const float* __restrict__ Dbuf,
-                                                               bf16_t* __restrict__ dqkv, int S, int Sp, int h, int stats_vec, int n_pairs, int n_blk) {
+                                                               bf16_t* __restrict__ dqkv, int S, int Sp, int h, int stats_vec, int n_pairs, int n_blk,
+                                                               const float* __restrict__ cosb, const float* __restrict__ sinb) {
   extern __shared__ u32x4 lds[];
   int pair, comb;
   causal_block_map(blockIdx.x, n_pairs, (n_blk + 1) / 2, pair, comb);
@@ -668,8 +698,8 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkv_kernel(const bf16_t* __re
   for (int part = 0; part < 2; ++part) {
     const int kblk = part == 0 ? comb : n_blk - 1 - comb;
     if (part == 1 && kblk == comb) break;
-    if (wave >= 4) attn_bwd_dkv_part<DH, true>(lds, qkv, qt_at, dO, dot_at, lse, Dbuf, dqkv, S, Sp, h, stats_vec, head, b, kblk, lane, wave);
-    else attn_bwd_dkv_part<DH, false>(lds, qkv, qt_at, dO, dot_at, lse, Dbuf, dqkv, S, Sp, h, stats_vec, head, b, kblk, lane, wave);
+    if (wave >= 4) attn_bwd_dkv_part<DH, true>(lds, qkv, qt_at, dO, dot_at, lse, Dbuf, dqkv, S, Sp, h, stats_vec, head, b, kblk, lane, wave, cosb, sinb);
+    else attn_bwd_dkv_part<DH, false>(lds, qkv, qt_at, dO, dot_at, lse, Dbuf, dqkv, S, Sp, h, stats_vec, head, b, kblk, lane, wave, cosb, sinb);
   }
 }
 
@@ -694,7 +724,7 @@ static int fwd_launch(hipStream_t st, const void* qkv, void* o, float* lse, void
 }
 template <int DH>
 static int bwd_launch(hipStream_t st, const void* qkv, const void* o, const float* lse, const void* dO, void* dqkv, float* Dbuf,
-                      void* at0, void* at1, void* at2, int B, int S, int h) {
+                      void* at0, void* at1, void* at2, int B, int S, int h, const float* cosb, const float* sinb) {
   constexpr int DQ_LDS = 2 * (2 * 64 * (DH / 8) + DH * 8) * 16;
   constexpr int DKV_LDS = (4 * (64 * (DH / 8) + DH * 8) + 2 * (2 * 4 * 2 * 64)) * 16;          // two V sets, two K sets, two P mailboxes
   static bool ok = set_lds(attn_bwd_dq_kernel<DH>, DQ_LDS) && set_lds(attn_bwd_dkv_kernel<DH>, DKV_LDS);
@@ -707,9 +737,9 @@ static int bwd_launch(hipStream_t st, const void* qkv, const void* o, const floa
   const int nb_kv = (S + 127) / 128, nb_dq = (S + 255) / 256;
   const int stats_vec = (S % 4 == 0) && ((reinterpret_cast<uintptr_t>(lse) | reinterpret_cast<uintptr_t>(Dbuf)) & 15) == 0;          // 16-byte loads of lse / D
   attn_bwd_dq_kernel<DH><<<dim3(B * h * ((nb_dq + 1) / 2)), 512, DQ_LDS, st>>>((const bf16_t*)qkv, (const bf16_t*)at0, (const bf16_t*)dO, lse, Dbuf, (bf16_t*)dqkv, S, Sp, h,
-                                                                 B * h, nb_dq);
+                                                                 B * h, nb_dq, cosb, sinb);
   attn_bwd_dkv_kernel<DH><<<dim3(B * h * ((nb_kv + 1) / 2)), 512, DKV_LDS, st>>>((const bf16_t*)qkv, (const bf16_t*)at1, (const bf16_t*)dO, (const bf16_t*)at2, lse, Dbuf,
-                                                      (bf16_t*)dqkv, S, Sp, h, stats_vec, B * h, nb_kv);
+                                                      (bf16_t*)dqkv, S, Sp, h, stats_vec, B * h, nb_kv, cosb, sinb);
   return 0;
 }
 
@@ -718,13 +748,16 @@ int k_attn_fwd_mfma(hipStream_t st, const void* qkv, void* o, float* lse, void* 
   if (!scratch || (dh != 64 && dh != 128) || S < 1) return 1;
   return dh == 64 ? fwd_launch<64>(st, qkv, o, lse, scratch, B, S, h) : fwd_launch<128>(st, qkv, o, lse, scratch, B, S, h);
 }
+// rope_cos / rope_sin ([S x dh/2] fp32, both or neither): dq and dk are returned with respect to the UN-rotated q and k
+// (the inverse rotation is applied to the accumulators before they are stored)
 int k_attn_bwd_mfma(hipStream_t st, const void* qkv, const void* o, const float* lse, const void* dO, void* dqkv, float* Dbuf,
-                    void* scratch, int B, int S, int h, int dh) {
-  if (!scratch || (dh != 64 && dh != 128) || S < 1) return 1;
+                    void* scratch, int B, int S, int h, int dh, const float* rope_cos, const float* rope_sin) {
+  if (!scratch || (dh != 64 && dh != 128) || S < 1 || (rope_cos == nullptr) != (rope_sin == nullptr)) return 1;
+  if (((uintptr_t)rope_cos | (uintptr_t)rope_sin) & 15) return 1;
   const size_t n = attn_scratch_elems(B, S, h, dh);
   bf16_t* s0 = (bf16_t*)scratch;
-  return dh == 64 ? bwd_launch<64>(st, qkv, o, lse, dO, dqkv, Dbuf, s0, s0 + n, s0 + 2 * n, B, S, h)
-                  : bwd_launch<128>(st, qkv, o, lse, dO, dqkv, Dbuf, s0, s0 + n, s0 + 2 * n, B, S, h);
+  return dh == 64 ? bwd_launch<64>(st, qkv, o, lse, dO, dqkv, Dbuf, s0, s0 + n, s0 + 2 * n, B, S, h, rope_cos, rope_sin)
+                  : bwd_launch<128>(st, qkv, o, lse, dO, dqkv, Dbuf, s0, s0 + n, s0 + 2 * n, B, S, h, rope_cos, rope_sin);
 }
 
 }  // namespace pp

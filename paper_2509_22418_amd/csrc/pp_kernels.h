@@ -78,6 +78,7 @@ void gemm_set_variant(int v);          // 0: register-staged MFMA GEMM, 1: direc
 size_t attn_scratch_elems(int B, int S, int h, int dh);
 int k_attn_fwd_mfma(hipStream_t st, const void* qkv, void* o, float* lse, void* scratch, int B, int S, int h, int dh);
 int k_attn_bwd_mfma(hipStream_t st, const void* qkv, const void* o, const float* lse, const void* dO, void* dqkv, float* Dbuf,
-                    void* scratch, int B, int S, int h, int dh);
+                    void* scratch, int B, int S, int h, int dh,
+                    const float* rope_cos, const float* rope_sin);          // tables given: dq, dk come out w.r.t. the un-rotated q, k
 
 }  // namespace pp

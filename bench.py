@@ -78,7 +78,7 @@ def run_leg(torch, pp, gen, cfg, weights, mask, batches, steps, warmup, time_gem
     return dict(seconds=dt, loss=loss, gemm=gt, counters=cnt, memory=mem, peak_alloc=peak_alloc, outer=outer_res)
 
 
-def time_outer_step(torch, pp, gen, m, seed, iters=50):
+def time_outer_step(torch, pp, gen, m, seed, iters=100):
     """Config 5: the node's share of the outer step on the trainable subset of the model that just ran its local
     steps (theta_l = its current bf16 weights): delta, add the on-device sum of 31 seeded N(0, 1e-4) deltas, divide by
     the count, Nesterov update (lr 0.7, momentum 0.9).  HBM-bound: 24 algorithmic bytes per element."""

@@ -98,3 +98,38 @@ def test_ragged_batch_and_ignored_targets():
     # opt == NULL: no update happened
     assert frozen_bytes_equal(cfg, m, weights, dict(gen.ffn_slice_mask(cfg, 0, 4), ffn_lo=0, ffn_hi=0)) == []
     m.close()
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_degenerate_batches(dtype):
+    """The method's degenerate inputs: a single token (B = S = 1: one key per query, softmax of one element), and a batch
+    whose targets are all ignored (no valid position: the loss is 0 by the mean-over-valid-positions convention, every
+    gradient is 0 and an AdamW step with zero gradients only applies the decoupled weight decay)."""
+    cfg = gen.make_config("tiny", dtype=dtype)
+    weights = gen.make_weights(cfg, seed=4)
+    mask = gen.paper_mlp_mask(cfg, 0, 4)
+    tol = 1e-5 if dtype == "fp32" else 1e-2
+    # one token
+    tok, tgt = np.array([[5]], dtype=np.int32), np.array([[7]], dtype=np.int32)
+    m = make_gpu_model(cfg, weights, mask)
+    lg = float(m.step(*m.upload_tokens(tok, tgt), None).item())
+    g_gpu = m.get_state("g")
+    params = O.to_f64(weights)
+    loss_ref, cache = O.forward(cfg, params, tok, tgt)
+    g_ref = O.masked_gradient(cfg, params, cache, mask)
+    assert abs(lg - loss_ref) <= tol * abs(loss_ref)
+    assert cosine(g_gpu, g_ref) >= (0.99999 if dtype == "fp32" else 0.999)
+    # nothing to predict
+    tok, tgt = gen.make_tokens(cfg, seed=4, batch=2, seq=9)
+    tgt[:] = -1
+    lg = float(m.step(*m.upload_tokens(tok, tgt), None).item())
+    assert lg == 0.0
+    assert not np.any(m.get_state("g"))
+    p_before = m.get_state("p").copy()
+    m.step(*m.upload_tokens(tok, tgt), HP)
+    tr = O.LocalTrainer(cfg, weights, mask)
+    loss_o, g_o = tr.step(tok, tgt, HP)
+    assert loss_o == 0.0 and not np.any(g_o)
+    np.testing.assert_allclose(m.get_state("p"), tr.master, rtol=1e-6, atol=1e-9)
+    assert np.any(m.get_state("p") != p_before)          # decayed
+    m.close()

@@ -44,6 +44,59 @@ def closed_form_flops(cfg, B, S, rho):
     return fwd, bwd
 
 
+class PowerSampler:
+    """Board power as the driver reports it (hwmon `power1_input`, microwatts) sampled every 20 ms from a thread while
+    the timed steps run; `power1_cap` is the board's limit.  Reported because the matrix kernels of this path run
+    against that limit (their clock drops under it), so energy per step is what bounds the step time."""
+
+    def __init__(self):
+        import glob
+        self.path = self.cap = None
+        for hw in sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*")):
+            if os.path.exists(os.path.join(hw, "power1_input")):
+                self.path = os.path.join(hw, "power1_input")
+                self.cap = self._read(os.path.join(hw, "power1_cap"))
+                break
+        self.samples = []
+        self._stop = False
+        self._th = None
+
+    @staticmethod
+    def _read(path):
+        try:
+            with open(path) as f:
+                return int(f.read().strip()) / 1e6
+        except (OSError, ValueError):
+            return None
+
+    def _run(self):
+        while not self._stop:
+            v = self._read(self.path)
+            if v is not None:
+                self.samples.append(v)
+            time.sleep(0.02)
+
+    def __enter__(self):
+        if self.path:
+            import threading
+            self._th = threading.Thread(target=self._run, daemon=True)
+            self._th.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop = True
+        if self._th:
+            self._th.join()
+
+    def report(self, seconds_per_step):
+        if not self.samples:
+            return None
+        mean = sum(self.samples) / len(self.samples)
+        return dict(mean_w=round(mean, 1), max_w=round(max(self.samples), 1), cap_w=self.cap, samples=len(self.samples),
+                    joules_per_step=round(mean * seconds_per_step, 2),
+                    source="hwmon power1_input, sampled every 20 ms over the timed steps (the driver's reading is itself smoothed)")
+
+
 def run_leg(torch, pp, gen, cfg, weights, mask, batches, steps, warmup, time_gemm, outer=False, seed=0):
     torch.cuda.synchronize()
     torch.cuda.empty_cache()
@@ -58,11 +111,12 @@ def run_leg(torch, pp, gen, cfg, weights, mask, batches, steps, warmup, time_gem
     if time_gemm:
         m.set_option("time_gemm", 1)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(steps):
-        m.step(*dev[i % len(dev)], HP)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    with PowerSampler() as power:
+        t0 = time.perf_counter()
+        for i in range(steps):
+            m.step(*dev[i % len(dev)], HP)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
     loss = float(m.loss.item())
     gt = m.gemm_timing() if time_gemm else None
     if time_gemm:
@@ -75,7 +129,8 @@ def run_leg(torch, pp, gen, cfg, weights, mask, batches, steps, warmup, time_gem
         outer_res = time_outer_step(torch, pp, gen, m, seed)
     m.close()
     del m
-    return dict(seconds=dt, loss=loss, gemm=gt, counters=cnt, memory=mem, peak_alloc=peak_alloc, outer=outer_res)
+    return dict(seconds=dt, loss=loss, gemm=gt, counters=cnt, memory=mem, peak_alloc=peak_alloc, outer=outer_res,
+                power=power.report(dt / steps))
 
 
 def time_outer_step(torch, pp, gen, m, seed, iters=100):
@@ -206,7 +261,8 @@ def main():
             gemm_tflops=round(r["gemm"]["flops"] / (r["gemm"]["ms"] * 1e-3) / 1e12, 1) if r["gemm"]["ms"] > 0 else None,
             gemm_ms_per_step=round(r["gemm"]["ms"] / args.steps, 3), gemm_launches_per_step=r["gemm"]["launches"] // args.steps,
             n_trainable=r["counters"]["n_trainable"], adamw_bytes=r["counters"]["adamw_bytes"],
-            hbm_bytes=r["memory"], peak_allocated_gb=round(r["peak_alloc"] / 2 ** 30, 3), final_loss=round(r["loss"], 5))
+            hbm_bytes=r["memory"], peak_allocated_gb=round(r["peak_alloc"] / 2 ** 30, 3), final_loss=round(r["loss"], 5),
+            board_power=r["power"])
         if r["outer"]:
             outer_step = r["outer"]
         log(f"[bench] leg {name}: {results[name]['tokens_per_s']} tokens/s, {ms:.2f} ms/step, "
@@ -236,6 +292,7 @@ def main():
                                "Zipf(1.1) tokens, N(0,0.02) weights",
                    "global_batch": B, "seq_len": S, "trainable_fraction_of_ffn": f"1/{n_slices}"},
         "step_mfma_frac": mr["step_mfma_frac"], "peak_hbm_gb": mr["peak_allocated_gb"],
+        "board_power": mr["board_power"],
         "roofline": roofline, "cpu_baseline": cpu, "outer_step": outer_step, "legs": results,
     }
     print(json.dumps(out))

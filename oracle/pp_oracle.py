@@ -17,6 +17,8 @@ What it computes (paper: "Partial Parameter Updates", Algorithm 1 and Section 2.
                          gradients only for trainable slices, input gradients through ALL slices
                          and ALL heads, and nothing propagated below the lowest trainable
                          parameter.  Counts the matmul FLOPs it executes.
+                         With jacobian_extra: the detach-all-but-k (+ random) ablation of
+                         Appendix "Additional Results".
   * adamw_update():      InnerOpt of Alg. 1 (decoupled AdamW, Experimental Setup) applied to
                          theta[I_train] only; frozen coordinates are not touched at all (no
                          weight decay either).
@@ -33,6 +35,7 @@ Pins (tests/test_oracle_*.py): central finite differences for every tensor; libr
 (rms_norm, scaled-dot-product attention, cross entropy, AdamW, Nesterov SGD) on the cases that
 reduce to them; closed forms (rotary, AdamW step 1, Nesterov step 1, loss ~ ln V at init);
 invariants (causality, slice additivity of the FFN, masked == slice of full, frozen unchanged);
+the detach ablation against library autograd with the dropped units' activations detached;
 FLOP counter == closed form; the paper's FLOP formulas reproduce its "15% fewer FLOPs" and its
 rho=1 identity; Table 1's trainable-parameter column.
 Parity unpinned: Table 1 perplexities / memory GB and the 0.44 s step time (need the paper's
@@ -292,7 +295,7 @@ def masked_gradient(cfg, params, cache, mask):
 
 
 # =============================================================================== backward (restricted)
-def backward_restricted(cfg, params, cache, mask):
+def backward_restricted(cfg, params, cache, mask, jacobian_extra=None):
     """Restricted backward.  Returns (packed gradient over I_train, info) where info holds the
     executed matmul FLOPs of the backward ('flops_bwd', causal pairs counted exactly) and the
     activation gradients it produced (for tests).
@@ -300,7 +303,14 @@ def backward_restricted(cfg, params, cache, mask):
     Weight gradients are formed only for trainable row blocks; input gradients always run through
     every FFN slice and every head; the chain stops as soon as no trainable parameter lies below.
     At the layer where the FFN slice is the lowest trainable thing, only the slice's columns of
-    dA are formed (dW of the gate/up slice needs nothing else)."""
+    dA are formed (dW of the gate/up slice needs nothing else).
+
+    jacobian_extra = None is the method.  A (lo, hi) range of FFN hidden units (possibly empty)
+    switches to the ablation of Appendix "Additional Results": the FFN's input gradient is summed
+    only over the trainable slice k ("detach-all-but-k") and over the units lo..hi-1 of one more
+    slice g ("... + random"; the caller draws g); every other unit's dL/dH is taken as zero.
+    SwiGLU stands where the appendix writes a ReLU MLP: the mask I(H > 0) becomes the SwiGLU
+    derivative.  Weight gradients, attention and everything else are unchanged."""
     B, S = cache["B"], cache["S"]
     T = B * S
     d, h, L, F, V = cfg["d_model"], cfg["n_heads"], cfg["n_layers"], cfg["d_ff"], cfg["vocab"]
@@ -350,7 +360,14 @@ def backward_restricted(cfg, params, cache, mask):
                     g[p + "wd"] = c["a"][:, fl:fh].T @ G
                     flops += 2 * T * d * (fh - fl)
                 dA = G @ params[p + "wd"][cols].T
-                flops += 2 * T * d * nc
+                nj = nc                # hidden units that enter the input Jacobian
+                if jacobian_extra is not None and below_ffn_w:
+                    kept = np.zeros(F, dtype=bool)
+                    kept[fl:fh] = True
+                    kept[jacobian_extra[0]:jacobian_extra[1]] = True
+                    dA = dA * kept[None, :]
+                    nj = int(kept.sum())
+                flops += 2 * T * d * nj
                 gg, uu = c["g"][:, cols], c["u"][:, cols]
                 sg = 1.0 / (1.0 + np.exp(-gg))
                 dU = dA * (gg * sg)
@@ -362,7 +379,7 @@ def backward_restricted(cfg, params, cache, mask):
                     flops += 4 * T * d * (fh - fl)
                 if below_ffn_w:
                     dn2 = dG @ params[p + "wg"] + dU @ params[p + "wu"]
-                    flops += 4 * T * d * F
+                    flops += 4 * T * d * nj
             if not below_ffn_w:
                 break
             dxm_n, dg2 = rmsnorm_bwd(dn2, c["xm"], c["rstd2"], params[p + "ffn_norm"])

@@ -241,6 +241,82 @@ def test_backward_stops_at_lowest_trainable_parameter():
     assert info["dx"] == {} and info["flops_bwd"] == 2 * cfg["batch"] * cfg["seq"] * cfg["d_model"] * cfg["vocab"]
 
 
+# ------------------------------------------------------------------ the detach ablation (Appendix "Additional Results")
+def _autograd_model_loss(cfg, tparams, tok, tgt, kept):
+    """The decoder written again with library tensor ops (fp64, autograd), the FFN activations of the hidden units
+    outside `kept` detached from the graph: their forward value is used, their Jacobian is dropped."""
+    F_ = torch.nn.functional
+    B, S = tok.shape
+    d, h, L = cfg["d_model"], cfg["n_heads"], cfg["n_layers"]
+    dh = d // h
+    half = dh // 2
+    pos = torch.arange(S, dtype=torch.float64)[:, None]
+    ang = pos * cfg["rope_base"] ** (-2.0 * torch.arange(half, dtype=torch.float64) / dh)[None, :]
+    cos, sin = torch.cos(ang)[None, :, None, :], torch.sin(ang)[None, :, None, :]
+
+    def rot(t):
+        a, b = t[..., :half], t[..., half:]
+        return torch.cat([a * cos - b * sin, a * sin + b * cos], dim=-1)
+
+    keep = torch.zeros(cfg["d_ff"], dtype=torch.bool)
+    for lo, hi in kept:
+        keep[lo:hi] = True
+    x = tparams["embed"][torch.from_numpy(tok.reshape(-1)).long()]
+    for l in range(L):
+        p = f"layers.{l}."
+        n1 = F_.rms_norm(x, (d,), weight=tparams[p + "attn_norm"], eps=cfg["rms_eps"])
+        qkv = n1 @ tparams[p + "wqkv"].T
+        q = rot(qkv[:, :d].reshape(B, S, h, dh)).transpose(1, 2)
+        k = rot(qkv[:, d:2 * d].reshape(B, S, h, dh)).transpose(1, 2)
+        v = qkv[:, 2 * d:].reshape(B, S, h, dh).transpose(1, 2)
+        o = F_.scaled_dot_product_attention(q, k, v, is_causal=True).transpose(1, 2).reshape(B * S, d)
+        xm = x + o @ tparams[p + "wo"].T
+        n2 = F_.rms_norm(xm, (d,), weight=tparams[p + "ffn_norm"], eps=cfg["rms_eps"])
+        a = F_.silu(n2 @ tparams[p + "wg"].T) * (n2 @ tparams[p + "wu"].T)
+        a = torch.where(keep[None, :], a, a.detach())
+        x = xm + a @ tparams[p + "wd"]
+    z = F_.rms_norm(x, (d,), weight=tparams["final_norm"], eps=cfg["rms_eps"]) @ tparams["lm_head"].T
+    return F_.cross_entropy(z, torch.from_numpy(tgt.reshape(-1)).long(), ignore_index=-1)
+
+
+@pytest.mark.parametrize("mname,extra", [("ffn_slice", None), ("ffn_slice", (48, 64)), ("paper_mlp", (0, 16)),
+                                         ("paper_mlp_heads", None)])
+def test_detach_ablation_matches_autograd_with_detached_units(mname, extra):
+    """detach-all-but-k (extra None -> empty range) and k + one more slice: the oracle's gradient over I_train equals
+    what library autograd gives when the activations of all other hidden units are detached."""
+    cfg = small_cfg(n_layers=3)
+    params, tok, tgt = setup(cfg)
+    mask = MASKS[mname](cfg)
+    ex = extra or (0, 0)
+    loss, cache = O.forward(cfg, params, tok, tgt)
+    g, info = O.backward_restricted(cfg, params, cache, mask, jacobian_extra=ex)
+    tparams = {k: torch.tensor(v, dtype=torch.float64, requires_grad=True) for k, v in params.items()}
+    tl = _autograd_model_loss(cfg, tparams, tok, tgt, [(mask["ffn_lo"], mask["ffn_hi"]), ex])
+    assert abs(float(tl.detach()) - loss) <= 1e-12 * abs(loss)
+    tl.backward()
+    ref = O.pack({k: v.grad.numpy() for k, v in tparams.items()}, O.mask_segments(cfg, mask))
+    np.testing.assert_allclose(g, ref, rtol=1e-9, atol=1e-13)
+    # and it is a different gradient from the method's (full Jacobian) wherever something trainable lies below an FFN
+    g_full, info_full = O.backward_restricted(cfg, params, cache, mask)
+    assert np.linalg.norm(g - g_full) > 1e-3 * np.linalg.norm(g_full)
+    # executed FLOPs: per layer whose FFN input gradient is formed, 6 T d (F - kept) fewer
+    T, d, F = tok.size, cfg["d_model"], cfg["d_ff"]
+    n_kept = (mask["ffn_hi"] - mask["ffn_lo"]) + (ex[1] - ex[0])
+    layers_with_dn = cfg["n_layers"] if mname != "ffn_slice" else cfg["n_layers"] - 1
+    assert info_full["flops_bwd"] - info["flops_bwd"] == layers_with_dn * 6 * T * d * (F - n_kept)
+
+
+def test_detach_ablation_with_every_unit_kept_is_the_method():
+    cfg = small_cfg()
+    params, tok, tgt = setup(cfg)
+    mask = gen.ffn_slice_mask(cfg, node=0, n_slices=4)
+    _, cache = O.forward(cfg, params, tok, tgt)
+    g0, i0 = O.backward_restricted(cfg, params, cache, mask)
+    g1, i1 = O.backward_restricted(cfg, params, cache, mask, jacobian_extra=(mask["ffn_hi"], cfg["d_ff"]))
+    np.testing.assert_array_equal(g0, g1)
+    assert i0["flops_bwd"] == i1["flops_bwd"]
+
+
 # ------------------------------------------------------------------ FLOP accounting
 @pytest.mark.parametrize("name,N", [("tiny", 4), ("tiny", 2)])
 def test_flop_counter_equals_closed_form(name, N):

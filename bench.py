@@ -29,9 +29,10 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def closed_form_flops(cfg, B, S, rho):
+def closed_form_flops(cfg, B, S, rho, detach=False):
     """Executed matmul FLOPs per step for the FFN-slice mask (rho < 1) or the all-trainable step (rho = 1):
-    forward L(8Td^2 + 4 P d + 6TdF) + 2TdV, P = causal pairs; backward per the mask."""
+    forward L(8Td^2 + 4 P d + 6TdF) + 2TdV, P = causal pairs; backward per the mask.
+    detach: the ablation in which only the trainable slice enters the FFN input gradient (6TdF -> 6TdF rho there)."""
     T = B * S
     d, L, F, V = cfg["d_model"], cfg["n_layers"], cfg["d_ff"], cfg["vocab"]
     P = B * S * (S + 1) // 2
@@ -39,7 +40,8 @@ def closed_form_flops(cfg, B, S, rho):
     if rho >= 1:
         return fwd, 2 * fwd
     Fk = F // round(1 / rho)
-    bwd = (2 * T * d * V + L * 6 * T * d * Fk + (L - 1) * 2 * T * d * F + 2 * T * d * Fk + (L - 1) * 4 * T * d * F
+    Fj = Fk if detach else F          # hidden units that enter the FFN input gradient
+    bwd = (2 * T * d * V + L * 6 * T * d * Fk + (L - 1) * 2 * T * d * Fj + 2 * T * d * Fk + (L - 1) * 4 * T * d * Fj
            + (L - 1) * (8 * T * d * d + 8 * P * d))
     return fwd, bwd
 
@@ -101,9 +103,12 @@ def run_leg(torch, pp, gen, cfg, weights, mask, batches, steps, warmup, time_gem
     torch.cuda.synchronize()
     torch.cuda.empty_cache()
     torch.cuda.reset_peak_memory_stats()
-    m = pp.LocalStepModel(cfg, mask)
+    detach = bool(cfg.get("detach_jacobian"))
+    m = pp.LocalStepModel({k: v for k, v in cfg.items() if k != "detach_jacobian"}, mask)
     m.load_weights(weights)
     m.set_mask()
+    if detach:
+        m.set_jacobian_slices(1)
     dev = [m.upload_tokens(t, g) for t, g in batches]
     for i in range(warmup):
         m.step(*dev[i % len(dev)], HP)
@@ -244,13 +249,15 @@ def main():
             legs.pop(1)
         # the paper's memory regime: full activation recomputation (same results bit for bit, less workspace, more time)
         legs.append(("rho=1/%d+recompute" % n_slices, gen.ffn_slice_mask(cfg, 0, n_slices), 1.0 / n_slices, dict(cfg, recompute=1)))
+        # the appendix's detach-all-but-k ablation (a different, cheaper gradient that the paper reports to diverge)
+        legs.append(("rho=1/%d+detach-ablation" % n_slices, gen.ffn_slice_mask(cfg, 0, n_slices), 1.0 / n_slices, dict(cfg, detach_jacobian=1)))
     results = {}
     outer_step = None
     for name, mask, rho, leg_cfg in legs:
         t1 = time.perf_counter()
         r = run_leg(torch, pp, gen, leg_cfg, weights, mask, batches, args.steps, args.warmup, time_gemm=True,
                     outer=(name == legs[0][0]), seed=args.seed)
-        fwd, bwd = closed_form_flops(cfg, B, S, rho)
+        fwd, bwd = closed_form_flops(cfg, B, S, rho, detach=bool(leg_cfg.get("detach_jacobian")))
         ms = r["seconds"] / args.steps * 1e3
         executed = r["counters"]["flops_fwd"] + r["counters"]["flops_bwd"]
         results[name] = dict(

@@ -123,6 +123,17 @@ int pp_set_trainable_mask(pp_model* m, const pp_mask* mask, void* state_dev, siz
 int pp_local_step(pp_model* m, const int32_t* tokens_dev, const int32_t* targets_dev, int32_t B, int32_t S,
                   const pp_adamw* opt, float* loss_dev);
 
+/* Ablation of Appendix "Additional Results" (off by default; the paper reports that it diverges or degrades):
+ * which FFN hidden units enter the INPUT gradient of every later pp_local_step.
+ *   mode 0: all of them (the method: frozen slices still carry the input gradient, Appendix "Partial Backward").
+ *   mode 1: "detach-all-but-k": only the trainable slice of the mask, plus the units [extra_lo, extra_hi) of one more
+ *           slice g ("detach-all-but-k + random"; the caller draws g and calls this before each step; an empty range
+ *           = no extra slice).  dL/dH of every other hidden unit is taken as zero; with SwiGLU the appendix's
+ *           activation mask I(H > 0) is the SwiGLU derivative.  Weight gradients and the forward pass are unchanged.
+ * Bounds must be multiples of 8 inside [0, d_ff] (PP_EINVAL otherwise).  pp_local_step then returns PP_EINVAL if the
+ * mask has no trainable FFN slice or if the extra range overlaps it.  Host-side state only; nothing is launched. */
+int pp_set_jacobian_slices(pp_model* m, int32_t mode, int32_t extra_lo, int32_t extra_hi);
+
 /* Node's share of the synchronisation (Algorithm 1, delta / normalisation / OuterOpt lines) on the
  * packed subset of n = trainable-element-count values: theta_l is read from the current weights in
  * storage dtype; theta_g_dev [n] fp32 global parameters and momentum_dev [n] fp32 are updated in place;

@@ -14,7 +14,7 @@ import numpy as np
 PP_F32, PP_BF16 = 0, 1
 PP_BYTES_PARAMS, PP_BYTES_STATE, PP_BYTES_WORKSPACE, PP_BYTES_SHADOW, PP_BYTES_ACTIVATIONS = range(5)
 EXPORTS = ["pp_query_bytes", "pp_init_model", "pp_set_tensor", "pp_get_tensor", "pp_set_trainable_mask", "pp_local_step",
-           "pp_outer_delta", "pp_outer_delta_group", "pp_synth_delta_sum", "pp_get_counters", "pp_get_gemm_timing", "pp_set_option", "pp_last_error", "pp_free",
+           "pp_set_jacobian_slices", "pp_outer_delta", "pp_outer_delta_group", "pp_synth_delta_sum", "pp_get_counters", "pp_get_gemm_timing", "pp_set_option", "pp_last_error", "pp_free",
            "pp_op_gemm_nt", "pp_op_attention_fwd", "pp_op_attention_bwd"]
 
 
@@ -73,6 +73,8 @@ def load_library():
     lib.pp_local_step.argtypes = [vp, vp, vp, i32, i32, C.POINTER(PPAdamW), vp]
     lib.pp_outer_delta.restype = C.c_int
     lib.pp_outer_delta.argtypes = [vp, vp, vp, vp, C.POINTER(PPOuter), vp]
+    lib.pp_set_jacobian_slices.restype = C.c_int
+    lib.pp_set_jacobian_slices.argtypes = [vp, i32, i32, i32]
     lib.pp_outer_delta_group.restype = C.c_int
     lib.pp_outer_delta_group.argtypes = [vp, i32, i32, i32, vp, vp, vp, C.POINTER(PPOuter), vp]
     lib.pp_synth_delta_sum.restype = C.c_int
@@ -142,6 +144,10 @@ def pp_set_trainable_mask(h, mask: PPMask, state_ptr: int, state_bytes: int):
 
 def pp_local_step(h, tokens_ptr: int, targets_ptr: int, B: int, S: int, opt, loss_ptr: int):
     _check(load_library().pp_local_step(h, tokens_ptr, targets_ptr, B, S, None if opt is None else C.byref(opt), loss_ptr), "pp_local_step")
+
+
+def pp_set_jacobian_slices(h, mode: int, extra_lo: int = 0, extra_hi: int = 0):
+    _check(load_library().pp_set_jacobian_slices(h, mode, extra_lo, extra_hi), "pp_set_jacobian_slices")
 
 
 def pp_outer_delta_group(h, layer_lo: int, layer_hi: int, ends: int, theta_g_ptr: int, momentum_ptr: int, others_ptr, opt: PPOuter, delta_out_ptr):
@@ -300,6 +306,9 @@ class LocalStepModel:
 
     def set_option(self, key: str, value: int):
         pp_set_option(self.h, key, value)
+
+    def set_jacobian_slices(self, mode: int, extra_lo: int = 0, extra_hi: int = 0):
+        pp_set_jacobian_slices(self.h, mode, extra_lo, extra_hi)
 
     def gemm_timing(self):
         return pp_get_gemm_timing(self.h)

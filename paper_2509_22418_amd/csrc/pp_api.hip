@@ -163,6 +163,7 @@ struct pp_model {
   float *sp = nullptr, *sm = nullptr, *sv = nullptr, *sg = nullptr;
   long step = 0;
   int force_plain = 0;
+  int jac_mode = 0, jac_lo = 0, jac_hi = 0;          // ablation: FFN input Jacobian over the trainable slice (+ units jac_lo..jac_hi-1) only
   double flops_fwd = 0, flops_bwd = 0, flops_recompute = 0, adamw_bytes = 0;
   double* flop_acc = nullptr;
   // optional GEMM timing: one event pair per GEMM launch, summed by pp_get_gemm_timing
@@ -340,6 +341,16 @@ extern "C" int pp_set_option(pp_model* m, const char* key, int64_t value) {
     return PP_OK;
   }
   return fail(PP_EINVAL, std::string("pp_set_option: unknown key ") + key);
+}
+
+extern "C" int pp_set_jacobian_slices(pp_model* m, int32_t mode, int32_t extra_lo, int32_t extra_hi) {
+  if (!m) return fail(PP_EINVAL, "pp_set_jacobian_slices: NULL");
+  if (mode != 0 && mode != 1) return fail(PP_EINVAL, "pp_set_jacobian_slices: mode must be 0 (full Jacobian) or 1 (trainable slice + extra range only)");
+  if (mode == 0) { m->jac_mode = 0; m->jac_lo = m->jac_hi = 0; return PP_OK; }
+  if (extra_lo < 0 || extra_hi < extra_lo || extra_hi > m->cfg.d_ff) return fail(PP_EINVAL, "pp_set_jacobian_slices: extra range outside [0, d_ff]");
+  if (extra_lo % 8 || extra_hi % 8) return fail(PP_EINVAL, "pp_set_jacobian_slices: extra range bounds must be multiples of 8");
+  m->jac_mode = 1; m->jac_lo = extra_lo; m->jac_hi = extra_hi;
+  return PP_OK;
 }
 
 // ------------------------------------------------------------------------------------------------ tensor I/O
@@ -542,6 +553,11 @@ extern "C" int pp_local_step(pp_model* m, const int32_t* tokens_dev, const int32
   const Layout& ly = m->lay;
   const WsPlan& w = m->ws;
   const Mask& mk = m->mask;
+  if (m->jac_mode == 1) {
+    if (!mk.ffn) return fail(PP_EINVAL, "pp_local_step: the reduced FFN Jacobian (pp_set_jacobian_slices) needs a mask with a trainable FFN slice");
+    if (m->jac_hi > m->jac_lo && m->jac_lo < mk.fh && mk.fl < m->jac_hi)
+      return fail(PP_EINVAL, "pp_local_step: the extra Jacobian range overlaps the trainable FFN slice");
+  }
   hipStream_t st = m->st;
   char* P = m->params;
   char* W = m->wsp;
@@ -631,17 +647,38 @@ extern "C" int pp_local_step(pp_model* m, const int32_t* tokens_dev, const int32
             k_transpose(st, dt, dx, d, tB, T, T, d);
             gemm_dw(m, tA, tB, g + find_seg(m, TK_WD, l)->packed_off, Fk, d, T);
           }
-          if (!gemm_swiglu_bwd(m, dx, canon(lb + ly.o_wd + (int64_t)c0 * d), ofs(act(l, w.a_gu), c0), ofs(dgu, c0), T, nc, F, d)) {
-            gemm_nt(m, dx, d, canon(lb + ly.o_wd + (int64_t)c0 * d), d, dA, nc, T, nc, d);        // dA = G Wd^T (rows c0..c1 of Wd)
-            k_swiglu_bwd(st, dt, act(l, w.a_gu), dA, nc, dgu, T, F, c0, c1);
-          }
+          // dG, dU of hidden units r0..r1-1 into their columns of dgu
+          auto ffn_dgu = [&](int r0, int r1) {
+            if (!gemm_swiglu_bwd(m, dx, canon(lb + ly.o_wd + (int64_t)r0 * d), ofs(act(l, w.a_gu), r0), ofs(dgu, r0), T, r1 - r0, F, d)) {
+              gemm_nt(m, dx, d, canon(lb + ly.o_wd + (int64_t)r0 * d), d, dA, r1 - r0, T, r1 - r0, d);        // dA = G Wd^T (rows r0..r1 of Wd)
+              k_swiglu_bwd(st, dt, act(l, w.a_gu), dA, r1 - r0, dgu, T, F, r0, r1);
+            }
+          };
+          const bool detach = below_ffn_w && m->jac_mode == 1;
+          if (!detach) ffn_dgu(c0, c1);
+          else { ffn_dgu(mk.fl, mk.fh); if (m->jac_hi > m->jac_lo) ffn_dgu(m->jac_lo, m->jac_hi); }
           if (mk.ffn) {      // [dWg_k; dWu_k] = [dG_k; dU_k]^T Xn
             k_transpose(st, dt, ofs(dgu, mk.fl), 2 * F, tA, T, T, Fk);
             k_transpose(st, dt, ofs(dgu, (size_t)F + mk.fl), 2 * F, ofs(tA, (size_t)Fk * T), T, T, Fk);
             k_transpose(st, dt, act(l, w.a_n2), d, tB, T, T, d);
             gemm_dw(m, tA, tB, g + find_seg(m, TK_WG, l)->packed_off, 2 * Fk, d, T);
           }
-          if (below_ffn_w) gemm_nt(m, dgu, 2 * F, shad(sb + ly.sh_wgu), 2 * F, dn, d, T, d, 2 * F);   // dXn over ALL slices
+          if (below_ffn_w && !detach) gemm_nt(m, dgu, 2 * F, shad(sb + ly.sh_wgu), 2 * F, dn, d, T, d, 2 * F);   // dXn over ALL slices
+          if (detach) {
+            // Appendix "Additional Results" (detach-all-but-k, + one more slice): dXn summed over the kept units only.
+            // Gate and up columns of a range are K-slices of the same product; the pieces are chained through the
+            // residual input, alternating between dn and the (idle) attention-gradient buffer so that the last lands in dn.
+            const int rng[2][2] = {{mk.fl, mk.fh}, {m->jac_lo, m->jac_hi}};
+            const int n_rng = m->jac_hi > m->jac_lo ? 2 : 1, n_pc = 2 * n_rng;
+            void* prev = nullptr;
+            for (int i = 0; i < n_pc; ++i) {
+              const size_t col = (size_t)(i & 1) * F + rng[i >> 1][0];
+              void* out = ((n_pc - 1 - i) & 1) ? dob : dn;
+              gemm_nt(m, ofs(dgu, col), 2 * F, ofs(shad(sb + ly.sh_wgu), col), 2 * F, out, d, T, d, rng[i >> 1][1] - rng[i >> 1][0],
+                      i ? EPI_ADD_RES : EPI_STORE, prev);
+              prev = out;
+            }
+          }
         }
         if (!below_ffn_w) break;
         if (mk.norms) k_rmsnorm_dgamma(st, dt, dn, act(l, w.a_xm), (float*)act(l, w.a_rstd2), dgpart, g + find_seg(m, TK_FFN_NORM, l)->packed_off, T, d);

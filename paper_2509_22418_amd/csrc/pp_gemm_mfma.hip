@@ -412,6 +412,19 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
         char* wbase = reinterpret_cast<char*>(lds) + wave * 16384;
 #pragma unroll
         for (int hi = 0; hi < 2; ++hi) {
+          // The saved operands of this half (R, and for the SwiGLU backward the second operand ldc2 columns further on)
+          // are requested first, all 16 (32) loads of the wave at once and from clamped addresses so that no branch
+          // separates them: they travel while the accumulators are turned around in LDS, instead of one dependent
+          // load -> compute -> store chain per row group.
+          uint2 rr[16], ru[16];
+#pragma unroll
+          for (int it = 0; it < 16; ++it) {
+            const int grow = min(m0 + wm * 128 + hi * 64 + 4 * it + (lane >> 4), M - 1);
+            const int gcol = min(n0 + wn * 64 + (lane & 15) * 4, N - 4);
+            const size_t off = (size_t)grow * ldc + gcol;
+            rr[it] = *reinterpret_cast<const uint2*>(R + off);
+            if constexpr (EPI == EPI_SWIGLU_BWD) ru[it] = *reinterpret_cast<const uint2*>(R + off + ldc2);
+          }
 #pragma unroll
           for (int ii = 0; ii < 4; ++ii) {
             const int i = 4 * hi + ii, row = ii * 16 + l16;
@@ -429,14 +442,13 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
             const int grow = m0 + wm * 128 + hi * 64 + row, gcol = n0 + wn * 64 + c * 4;
             if (grow < M && gcol < N) {
               const size_t off = (size_t)grow * ldc + gcol;
-              const uint2 rr = *reinterpret_cast<const uint2*>(R + off);
               if constexpr (EPI == EPI_SWIGLU_BWD) {
                 // the product is dL/da; R holds the saved gate at this column and the saved up ldc2 columns further on:
                 // dg = da u sig(g) (1 + g (1 - sig(g))) and du = da g sig(g) go to the same two places of C
-                const uint2 ru = *reinterpret_cast<const uint2*>(R + off + ldc2);
+                const uint2 rg = rr[it], rv = ru[it];
                 const float da[4] = {v.x, v.y, v.z, v.w};
-                const float gg[4] = {__uint_as_float(rr.x << 16), __uint_as_float(rr.x & 0xffff0000u), __uint_as_float(rr.y << 16), __uint_as_float(rr.y & 0xffff0000u)};
-                const float uu[4] = {__uint_as_float(ru.x << 16), __uint_as_float(ru.x & 0xffff0000u), __uint_as_float(ru.y << 16), __uint_as_float(ru.y & 0xffff0000u)};
+                const float gg[4] = {__uint_as_float(rg.x << 16), __uint_as_float(rg.x & 0xffff0000u), __uint_as_float(rg.y << 16), __uint_as_float(rg.y & 0xffff0000u)};
+                const float uu[4] = {__uint_as_float(rv.x << 16), __uint_as_float(rv.x & 0xffff0000u), __uint_as_float(rv.y << 16), __uint_as_float(rv.y & 0xffff0000u)};
                 float dg[4], du[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -450,9 +462,10 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
                 w.x = f32x2_to_bf16x2(du[0], du[1]); w.y = f32x2_to_bf16x2(du[2], du[3]);
                 *reinterpret_cast<uint2*>(C + off + ldc2) = w;
               } else {
+                const uint2 r0 = rr[it];
                 uint2 w;
-                w.x = f32x2_to_bf16x2(v.x + __uint_as_float(rr.x << 16), v.y + __uint_as_float(rr.x & 0xffff0000u));
-                w.y = f32x2_to_bf16x2(v.z + __uint_as_float(rr.y << 16), v.w + __uint_as_float(rr.y & 0xffff0000u));
+                w.x = f32x2_to_bf16x2(v.x + __uint_as_float(r0.x << 16), v.y + __uint_as_float(r0.x & 0xffff0000u));
+                w.y = f32x2_to_bf16x2(v.z + __uint_as_float(r0.y << 16), v.w + __uint_as_float(r0.y & 0xffff0000u));
                 *reinterpret_cast<uint2*>(C + off) = w;
               }
             }

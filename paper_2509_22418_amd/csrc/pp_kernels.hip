@@ -374,7 +374,74 @@ __global__ void cross_entropy_kernel(T* logits, const int32_t* __restrict__ targ
     row[i] = from_f32<T>(p * inv_n);
   }
 }
+// bf16 rows of up to 512 * 8 * NV logits, V % 8 == 0: the row lives in registers (NV 16-byte pieces per thread, loaded and
+// stored with consecutive lanes on consecutive pieces), so there is one HBM read, one HBM write and no LDS staging.
+template <int NV>
+__global__ __launch_bounds__(512) void cross_entropy_reg_kernel(bf16_t* logits, const int32_t* __restrict__ targets,
+                                                                const int32_t* __restrict__ n_valid, float* __restrict__ rowloss, int V) {
+  __shared__ float red[17];
+  const int t = blockIdx.x, nvec = V >> 3;
+  uint4* row = reinterpret_cast<uint4*>(logits + (size_t)t * V);
+  int tg = targets[t];
+  if (tg >= V) tg = -1;          // out-of-range targets are treated as ignored
+  if (tg < 0) {            // ignored position: zero gradient, zero loss (uniform branch per block)
+    for (int i = threadIdx.x; i < nvec; i += 512) row[i] = make_uint4(0, 0, 0, 0);
+    if (threadIdx.x == 0) rowloss[t] = 0.f;
+    return;
+  }
+  uint4 r[NV];
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    const int i = threadIdx.x + 512 * k;
+    r[k] = i < nvec ? row[i] : make_uint4(0xff80ff80u, 0xff80ff80u, 0xff80ff80u, 0xff80ff80u);          // -inf: no effect on max or sum
+  }
+  auto lo = [](uint32_t w) { return __uint_as_float(w << 16); };
+  auto hi = [](uint32_t w) { return __uint_as_float(w & 0xffff0000u); };
+  float mx = -INFINITY;
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    const uint32_t w[4] = {r[k].x, r[k].y, r[k].z, r[k].w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) mx = fmaxf(mx, fmaxf(lo(w[e]), hi(w[e])));
+  }
+  mx = block_max(mx, red);
+  float sum = 0.f;
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    const uint32_t w[4] = {r[k].x, r[k].y, r[k].z, r[k].w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) sum += __expf(lo(w[e]) - mx) + __expf(hi(w[e]) - mx);
+  }
+  sum = block_sum(sum, red);
+  const float inv_n = 1.0f / (float)max(*n_valid, 1);
+  const float inv_sum = 1.0f / sum;
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    const int i = threadIdx.x + 512 * k;
+    if (i >= nvec) continue;
+    const uint32_t w[4] = {r[k].x, r[k].y, r[k].z, r[k].w};
+    uint32_t o[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float p0 = __expf(lo(w[e]) - mx) * inv_sum, p1 = __expf(hi(w[e]) - mx) * inv_sum;
+      const int c = 8 * i + 2 * e;
+      if (c == tg) { rowloss[t] = (mx + logf(sum)) - lo(w[e]); p0 -= 1.0f; }
+      if (c + 1 == tg) { rowloss[t] = (mx + logf(sum)) - hi(w[e]); p1 -= 1.0f; }
+      o[e] = f32x2_to_bf16x2(p0 * inv_n, p1 * inv_n);
+    }
+    row[i] = make_uint4(o[0], o[1], o[2], o[3]);
+  }
+}
 int k_cross_entropy(hipStream_t st, int dtype, void* logits, const int32_t* targets, const int32_t* n_valid, float* rowloss, int T_, int V) {
+  if (dtype == 1 && V % 8 == 0 && V <= 512 * 8 * 8 && ((uintptr_t)logits & 15) == 0) {
+    const int nv = (V / 8 + 511) / 512;
+    bf16_t* lg = (bf16_t*)logits;
+    if (nv <= 1) cross_entropy_reg_kernel<1><<<T_, 512, 0, st>>>(lg, targets, n_valid, rowloss, V);
+    else if (nv <= 2) cross_entropy_reg_kernel<2><<<T_, 512, 0, st>>>(lg, targets, n_valid, rowloss, V);
+    else if (nv <= 4) cross_entropy_reg_kernel<4><<<T_, 512, 0, st>>>(lg, targets, n_valid, rowloss, V);
+    else cross_entropy_reg_kernel<8><<<T_, 512, 0, st>>>(lg, targets, n_valid, rowloss, V);
+    return 0;
+  }
   size_t smem = (size_t)V * (dtype == 0 ? 4 : 2);
   if (smem > 64 * 1024 - 256) return 1;
   PP_DISPATCH(dtype, cross_entropy_kernel<T><<<T_, 512, smem, st>>>((T*)logits, targets, n_valid, rowloss, V));

@@ -121,12 +121,29 @@ def test_1p3b_shape_step_matches_oracle_on_one_sequence():
     print("case 1p3b B=8 sampled", flush=True)
     tok8, tgt8 = gen.make_tokens(cfg, seed=1234)
     m8 = make_gpu_model(cfg, weights, mask)
+    # First the backward.  With every target outside the first 64 positions of sequence 5 ignored, the loss and hence
+    # every gradient depend on that prefix alone (ignored rows have dL/dz = 0, and causality keeps the prefix's
+    # activations independent of the rest), so the oracle gets the complete gradient over I_train from the 64 tokens
+    # while the library runs all 8 x 2048 positions through every kernel.
+    print("case 1p3b B=8 backward, loss on one prefix", flush=True)
+    npre, seq = 64, 5
+    tgt_m = np.full_like(tgt8, -1)
+    tgt_m[seq, :npre] = tgt8[seq, :npre]
+    loss_m = float(m8.step(*m8.upload_tokens(tok8, tgt_m), None).item())
+    g8 = m8.get_state("g")
+    loss_p, pcache = O.forward(cfg, params, tok8[seq:seq + 1, :npre], tgt_m[seq:seq + 1, :npre])
+    g_p, _ = O.backward_restricted(cfg, params, pcache, mask)
+    assert abs(loss_m - loss_p) <= 1e-2 * abs(loss_p), (loss_m, loss_p)
+    cosines = [cosine(g8[off:off + n], g_p[off:off + n]) for _, off, n in segment_slices(cfg, mask)]
+    print(f"loss gpu {loss_m:.5f} oracle {loss_p:.5f}; per-tensor gradient cosine min {min(cosines):.6f} mean {np.mean(cosines):.6f}", flush=True)
+    assert min(cosines) >= 0.999
+
+    # Then a full step with all targets and the update; forward checked on the same prefix.
     loss8 = float(m8.step(*m8.upload_tokens(tok8, tgt8), HP).item())
     cnt8 = m8.counters()
     B8, S8 = tok8.shape
     assert np.isfinite(loss8)
     assert cnt8["flops_fwd"] + cnt8["flops_bwd"] == O.flops_forward(cfg, B8, S8) + O.flops_backward_ffn_slice(cfg, B8, S8, 1.0 / 32)
-    npre, seq = 64, 5
     _, pc = O.forward(cfg, params, tok8[seq:seq + 1, :npre], tgt8[seq:seq + 1, :npre])
     d, T8 = cfg["d_model"], B8 * S8
     rows = slice(seq * S8, seq * S8 + npre)

@@ -163,7 +163,10 @@ int pp_get_counters(pp_model* m, double* flops_fwd, double* flops_bwd, double* a
 /* Options for tests and profiling.  "force_plain": 0 = automatic (MFMA kernels when shapes allow), 1 = force the
  * plain (non-MFMA) kernels.  "time_gemm": 1 = bracket every GEMM launch of later pp_local_step calls with a pair
  * of HIP events on the model's stream (host-side events only; no device memory), 0 = off; setting it resets the totals.
- * "gemm_variant" (process-wide; m may be NULL): 1 = direct-to-LDS MFMA GEMM (default), 0 = register-staged MFMA GEMM. */
+ * "gemm_variant" (process-wide; m may be NULL): 1 = direct-to-LDS MFMA GEMM (default), 0 = register-staged MFMA GEMM.
+ * "gemm_persistent" (process-wide; m may be NULL): 1 (default) = when a GEMM has more tiles than the GPU has compute
+ * units, one workgroup per unit walks several tiles and requests its next tile's first operands before the current
+ * tile's epilogue; 0 = one workgroup per tile.  Same results bit for bit. */
 int pp_set_option(pp_model* m, const char* key, int64_t value);
 
 /* Blocks until the stream is idle, then returns the summed duration (ms), matmul FLOPs and number of the GEMM

@@ -193,36 +193,43 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 2, wn = wave & 3;
   const int nb = tiles_m * tiles_n;
-  int pid = blockIdx.x;
-  if ((nb & 7) == 0) pid = (pid & 7) * (nb >> 3) + (pid >> 3);
-  constexpr int GROUP = 8;
-  const int per_group = GROUP * tiles_n;
-  const int group = pid / per_group;
-  const int first_m = group * GROUP;
-  const int gsz = min(tiles_m - first_m, GROUP);
-  const int in_group = pid - group * per_group;
-  const int tm = first_m + in_group % gsz, tn = in_group / gsz;
-  const int m0 = tm * BM, n0 = tn * BN;
   const int z = blockIdx.y;
   const size_t kbase = (size_t)z * Ksplit;
-
+  // Tile walk.  The grid's x extent may be smaller than the number of tiles: workgroup b then takes the tiles b,
+  // b + gridDim.x, ... one after the other (gridDim.x is a multiple of 8 in that case, so a workgroup's tiles all map to
+  // its own XCD below), and requests the first three units of its next tile before it starts the epilogue of the
+  // current one, so that neither the launch of a new workgroup nor the first trip to memory separates two tiles.
+  auto tile_of = [&](int vb, int& tm, int& tn) {
+    int pid = vb;
+    if ((nb & 7) == 0) pid = (pid & 7) * (nb >> 3) + (pid >> 3);          // XCD k = id % 8 owns a contiguous range of tiles
+    constexpr int GROUP = 8;
+    const int per_group = GROUP * tiles_n;
+    const int group = pid / per_group;
+    const int first_m = group * GROUP;
+    const int gsz = min(tiles_m - first_m, GROUP);
+    const int in_group = pid - group * per_group;
+    tm = first_m + in_group % gsz;
+    tn = in_group / gsz;
+  };
   // wave w fills rows 32w .. 32w+31 of a unit with four loads of 8 rows (8 lanes per 128-byte row) each
   const bf16_t* gA[4];
   const bf16_t* gB[4];
+  auto set_ptrs = [&](int tm, int tn) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int row = wave * 32 + i * 8 + (lane >> 3);
-    const int c = (lane & 7) ^ ((row >> 1) & 7);
-    gA[i] = A + (size_t)min(m0 + row, M - 1) * lda + kbase + c * 8;
-    if constexpr (EPI == EPI_SWIGLU) {
-      // panel rows 64q .. 64q+31 are rows of W_g, 64q+32 .. 64q+63 the same hidden units' rows of W_u (N = d_ff,
-      // B = [W_g; W_u]): a wave's 64 output columns then hold gate and up of 32 units in matching registers
-      const int unit = min(tn * (BN / 2) + (row >> 6) * 32 + (row & 31), N - 1);
-      gB[i] = B + ((size_t)((row >> 5) & 1) * N + unit) * ldb + kbase + c * 8;
-    } else {
-      gB[i] = B + (size_t)min(n0 + row, N - 1) * ldb + kbase + c * 8;
+    for (int i = 0; i < 4; ++i) {
+      const int row = wave * 32 + i * 8 + (lane >> 3);
+      const int c = (lane & 7) ^ ((row >> 1) & 7);
+      gA[i] = A + (size_t)min(tm * BM + row, M - 1) * lda + kbase + c * 8;
+      if constexpr (EPI == EPI_SWIGLU) {
+        // panel rows 64q .. 64q+31 are rows of W_g, 64q+32 .. 64q+63 the same hidden units' rows of W_u (N = d_ff,
+        // B = [W_g; W_u]): a wave's 64 output columns then hold gate and up of 32 units in matching registers
+        const int unit = min(tn * (BN / 2) + (row >> 6) * 32 + (row & 31), N - 1);
+        gB[i] = B + ((size_t)((row >> 5) & 1) * N + unit) * ldb + kbase + c * 8;
+      } else {
+        gB[i] = B + (size_t)min(tn * BN + row, N - 1) * ldb + kbase + c * 8;
+      }
     }
-  }
+  };
   const int wdst = wave * 32 * 8;          // chunk offset of this wave's rows inside a unit (wave-uniform)
   const int ns = Ksplit / DL_BK;
   auto issue = [&](const bf16_t* const (&g)[4], int s, int slot) {          // unit of super-step s (clamped) into `slot`
@@ -232,10 +239,22 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
     for (int i = 0; i < 4; ++i) __builtin_amdgcn_global_load_lds(PP_GPTR(g[i] + koff), PP_LPTR(dst + i * 64), 16, 0, 0);
   };
   auto m5 = [](int x) { return x >= DL_SLOTS ? x - DL_SLOTS : x; };
+
+  const int l16 = lane & 15, lq = lane >> 4, sw = (l16 >> 1) & 7;          // row in a 16-row block, 16-byte chunk within a 64-byte K32 piece
+  const int aRow = (wm * 128 + l16) * 8, bRow = (wn * 64 + l16) * 8;
+  // The epilogues turn the accumulators around in LDS patches of 8 KB per wave that live in ring slots 3 and 4, so that
+  // slots 0..2 can already receive the next tile's first units.
+  char* const wbase = reinterpret_cast<char*>(lds) + 3 * DL_UNIT_CHUNKS * 16 + wave * 8192;
+
+  int vb = blockIdx.x, tm, tn;
+  tile_of(vb, tm, tn);
+  set_ptrs(tm, tn);
   issue(gA, 0, 0); issue(gB, 0, 1); issue(gA, 1, 2);
   // Plain s_barrier (no fence): a workgroup fence would force vmcnt(0), i.e. wait for ALL loads in flight.  The only
   // LDS traffic here is DMA writes (tracked by vmcnt) and fragment reads (consumed by MFMAs before the barrier).
   __builtin_amdgcn_s_waitcnt(0x0F70 | 4);          // vmcnt(4): both units of super-step 0 have landed
+  for (;;) {
+  const int m0 = tm * BM, n0 = tn * BN;
   __builtin_amdgcn_s_barrier();
 
   // 16 x 16 x 32 MFMAs: on non-trivial operand data the matrix pipe is power-limited, and this shape sustains about
@@ -250,8 +269,6 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
 #pragma unroll
       for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
 
-  const int l16 = lane & 15, lq = lane >> 4, sw = (l16 >> 1) & 7;          // row in a 16-row block, 16-byte chunk within a 64-byte K32 piece
-  const int aRow = (wm * 128 + l16) * 8, bRow = (wn * 64 + l16) * 8;
   // A super-step of 64 K-elements = 2 MFMA K-steps of 32 = 4 slices of 16 MFMAs (one K-step x one half of the wave's 8 row
   // blocks of A).  Fragment registers are double-buffered: the reads of the next slice (4 A fragments, plus the 4 B
   // fragments when the K-step changes) are slotted between the MFMAs of the current one.
@@ -313,26 +330,38 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
     sa = na;
   }
 #undef PP_DL_INTERLEAVE
-  __builtin_amdgcn_s_waitcnt(0x0F70);              // drain the clamped tail loads before the LDS is released
+  // drain the clamped tail loads (and the fragment reads issued for a super-step that does not exist) and meet: after
+  // this barrier nobody reads the staged panels any more and nothing is on its way into them
+  __builtin_amdgcn_s_waitcnt(0x0070);
+  __builtin_amdgcn_s_barrier();
+  const int vb_next = vb + gridDim.x;
+  const bool has_next = vb_next < nb;
+  int tm_next = 0, tn_next = 0;
+  if (has_next) {
+    tile_of(vb_next, tm_next, tn_next);
+    set_ptrs(tm_next, tn_next);
+    issue(gA, 0, 0); issue(gB, 0, 1); issue(gA, 1, 2);
+  }
+  __builtin_amdgcn_sched_barrier(0);
 
+  // ---- epilogue: element r of accumulator (i, j) is output row m0 + wm*128 + 16 i + lane % 16,
+  //      column n0 + wn*64 + 16 j + 4 (lane / 16) + r
+  bool stored = false;
   if constexpr (EPI == EPI_SWIGLU) {
     // ---- fused SwiGLU epilogue.  acc[i][j] (j = 0, 1) and acc[i][j + 2] are gate and up pre-activations of hidden unit
     // u0 + 16 j + 4 (lane / 16) + r (u0 = tn*128 + wn*32) for output row m0 + wm*128 + 16 i + lane % 16.  Both are
     // rounded to bf16 and stored at columns u and N + u of C (ldc >= 2 N); a = silu(g) * u is formed from the ROUNDED
     // values -- exactly what a separate pass over the stored matrix would compute -- and stored at column u of C2.
-    // Each wave turns 64 rows at a time around in a private 16 KB LDS patch (64 rows x 256 bytes: gate | up | a | unused,
+    // Each wave turns 32 rows at a time around in its LDS patch (32 rows x 256 bytes: gate | up | a | unused,
     // 16-byte piece p of row r at p ^ (r & 15)), so that 4 lanes cover one 64-byte row segment of each output.
-    __builtin_amdgcn_s_waitcnt(0x0070);
-    __builtin_amdgcn_s_barrier();                  // every wave is done with the staged panels
     bf16_t* C = reinterpret_cast<bf16_t*>(Cv);
     bf16_t* C2 = const_cast<bf16_t*>(R);
-    char* wbase = reinterpret_cast<char*>(lds) + wave * 16384;
     const int u0 = tn * (BN / 2) + wn * 32;
 #pragma unroll
-    for (int hi = 0; hi < 2; ++hi) {
+    for (int qt = 0; qt < 4; ++qt) {
 #pragma unroll
-      for (int ii = 0; ii < 4; ++ii) {
-        const int i = 4 * hi + ii, row = ii * 16 + l16;
+      for (int ii = 0; ii < 2; ++ii) {
+        const int i = 2 * qt + ii, row = ii * 16 + l16;
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
           uint2 wg, wu, wa;
@@ -356,34 +385,29 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
         }
       }
 #pragma unroll
-      for (int it = 0; it < 8; ++it) {          // gate and up: 8 pieces per row, 8 rows per wave instruction
+      for (int it = 0; it < 4; ++it) {          // gate and up: 8 pieces per row, 8 rows per wave instruction
         const int row = 8 * it + (lane >> 3), pc = lane & 7;
         const uint4 v = *reinterpret_cast<const uint4*>(wbase + row * 256 + ((pc ^ (row & 15)) << 4));
-        const int grow = m0 + wm * 128 + hi * 64 + row, unit = u0 + (pc & 3) * 8;
+        const int grow = m0 + wm * 128 + qt * 32 + row, unit = u0 + (pc & 3) * 8;
         if (grow < M && unit < N) *reinterpret_cast<uint4*>(C + (size_t)grow * ldc + (size_t)(pc >> 2) * N + unit) = v;
       }
 #pragma unroll
-      for (int it = 0; it < 4; ++it) {          // a: 4 pieces per row, 16 rows per wave instruction
+      for (int it = 0; it < 2; ++it) {          // a: 4 pieces per row, 16 rows per wave instruction
         const int row = 16 * it + (lane >> 2), pc = 8 + (lane & 3);
         const uint4 v = *reinterpret_cast<const uint4*>(wbase + row * 256 + ((pc ^ (row & 15)) << 4));
-        const int grow = m0 + wm * 128 + hi * 64 + row, unit = u0 + (lane & 3) * 8;
+        const int grow = m0 + wm * 128 + qt * 32 + row, unit = u0 + (lane & 3) * 8;
         if (grow < M && unit < N) *reinterpret_cast<uint4*>(C2 + (size_t)grow * ldc2 + unit) = v;
       }
     }
-    return;
-  }
-  // ---- epilogue: element r of accumulator (i, j) is output row m0 + wm*128 + 16 i + lane % 16,
-  //      column n0 + wn*64 + 16 j + 4 (lane / 16) + r
-  if constexpr (!OUT_F32) {
+    stored = true;
+  } else if constexpr (!OUT_F32) {
     if ((N & 7) == 0 && (ldc & 7) == 0) {          // uniform: coalesced path through LDS
-      // Each wave turns its 128 x 64 sub-tile around in a private LDS patch, 64 rows at a time: 8-byte pieces
-      // (4 consecutive columns of one row) are written, 16-byte row chunks are read back so that 8 lanes cover one
-      // 128-byte row segment of C (and of the residual).  Chunk c of row r sits at c ^ ((r >> 1) & 7).
-      __builtin_amdgcn_s_waitcnt(0x0070);
-      __builtin_amdgcn_s_barrier();                  // every wave is done with the staged panels
+      // Each wave turns its 128 x 64 sub-tile around in its LDS patch: 8-byte pieces (4 consecutive columns of one row)
+      // are written, 16-byte row chunks are read back so that 8 lanes cover one 128-byte row segment of C (and of the
+      // residual).
       bf16_t* C = reinterpret_cast<bf16_t*>(Cv);
       if constexpr (EPI == EPI_STORE) {
-        char* wbase = reinterpret_cast<char*>(lds) + wave * 8192;          // 64 rows x 128 bytes (bf16)
+        // 64 rows x 128 bytes (bf16) at a time; chunk c of row r sits at c ^ ((r >> 1) & 7)
 #pragma unroll
         for (int hi = 0; hi < 2; ++hi) {
 #pragma unroll
@@ -407,27 +431,27 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
           }
         }
       } else {
-        // residual add (or SwiGLU backward): the result is formed in fp32 and rounded once, so the patch holds floats (64 rows x 256 bytes,
-        // 16-byte piece p of row r at p ^ (r & 15)); 16 lanes then cover one 128-byte row segment of R and of C
-        char* wbase = reinterpret_cast<char*>(lds) + wave * 16384;
+        // residual add (or SwiGLU backward): the result is formed in fp32 and rounded once, so the patch holds floats
+        // (32 rows x 256 bytes at a time, 16-byte piece p of row r at p ^ (r & 15)); 16 lanes then cover one 128-byte
+        // row segment of R and of C
 #pragma unroll
-        for (int hi = 0; hi < 2; ++hi) {
-          // The saved operands of this half (R, and for the SwiGLU backward the second operand ldc2 columns further on)
-          // are requested first, all 16 (32) loads of the wave at once and from clamped addresses so that no branch
+        for (int qt = 0; qt < 4; ++qt) {
+          // The saved operands of this quarter (R, and for the SwiGLU backward the second operand ldc2 columns further
+          // on) are requested first, all 8 (16) loads of the wave at once and from clamped addresses so that no branch
           // separates them: they travel while the accumulators are turned around in LDS, instead of one dependent
           // load -> compute -> store chain per row group.
-          uint2 rr[16], ru[16];
+          uint2 rr[8], ru[8];
 #pragma unroll
-          for (int it = 0; it < 16; ++it) {
-            const int grow = min(m0 + wm * 128 + hi * 64 + 4 * it + (lane >> 4), M - 1);
+          for (int it = 0; it < 8; ++it) {
+            const int grow = min(m0 + wm * 128 + qt * 32 + 4 * it + (lane >> 4), M - 1);
             const int gcol = min(n0 + wn * 64 + (lane & 15) * 4, N - 4);
             const size_t off = (size_t)grow * ldc + gcol;
             rr[it] = *reinterpret_cast<const uint2*>(R + off);
             if constexpr (EPI == EPI_SWIGLU_BWD) ru[it] = *reinterpret_cast<const uint2*>(R + off + ldc2);
           }
 #pragma unroll
-          for (int ii = 0; ii < 4; ++ii) {
-            const int i = 4 * hi + ii, row = ii * 16 + l16;
+          for (int ii = 0; ii < 2; ++ii) {
+            const int i = 2 * qt + ii, row = ii * 16 + l16;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
               const int q = 4 * j + lq;          // 16-byte piece (4 floats) index within the 256-byte row
@@ -436,10 +460,10 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
             }
           }
 #pragma unroll
-          for (int it = 0; it < 16; ++it) {
+          for (int it = 0; it < 8; ++it) {
             const int row = 4 * it + (lane >> 4), c = lane & 15;
             const float4 v = *reinterpret_cast<const float4*>(wbase + row * 256 + ((c ^ (row & 15)) << 4));
-            const int grow = m0 + wm * 128 + hi * 64 + row, gcol = n0 + wn * 64 + c * 4;
+            const int grow = m0 + wm * 128 + qt * 32 + row, gcol = n0 + wn * 64 + c * 4;
             if (grow < M && gcol < N) {
               const size_t off = (size_t)grow * ldc + gcol;
               if constexpr (EPI == EPI_SWIGLU_BWD) {
@@ -472,39 +496,59 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
           }
         }
       }
-      return;
+      stored = true;
     }
   }
-  const int row_base = m0 + wm * 128 + l16;
-  const int col_base = n0 + wn * 64 + 4 * lq;
-  const bool n_vec_ok = (N % 4 == 0) && (ldc % 4 == 0);
+  if (!stored) {          // fp32 output (weight gradients, split-K partials) and shapes the vector paths do not take
+    const int row_base = m0 + wm * 128 + l16;
+    const int col_base = n0 + wn * 64 + 4 * lq;
+    const bool n_vec_ok = (N % 4 == 0) && (ldc % 4 == 0);
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int row = row_base + i * 16;
-    if (row >= M) continue;
+    for (int i = 0; i < 8; ++i) {
+      const int row = row_base + i * 16;
+      if (row >= M) continue;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int col = col_base + j * 16;
-      if (col >= N) continue;
-      float v[4] = {acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]};
-      if constexpr (OUT_F32) {
-        float* C = reinterpret_cast<float*>(Cv) + (size_t)z * (size_t)M * (size_t)ldc + (size_t)row * ldc + col;
-        if (n_vec_ok) *reinterpret_cast<float4*>(C) = make_float4(v[0], v[1], v[2], v[3]);
-        else for (int e = 0; e < 4 && col + e < N; ++e) C[e] = v[e];
-      } else {
-        bf16_t* C = reinterpret_cast<bf16_t*>(Cv) + (size_t)row * ldc + col;
-        for (int e = 0; e < 4 && col + e < N; ++e) {
-          float x = v[e];
-          if constexpr (EPI == EPI_ADD_RES) x += to_f32(R[(size_t)row * ldc + col + e]);
-          C[e] = from_f32<bf16_t>(x);
+      for (int j = 0; j < 4; ++j) {
+        const int col = col_base + j * 16;
+        if (col >= N) continue;
+        float v[4] = {acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]};
+        if constexpr (OUT_F32) {
+          float* C = reinterpret_cast<float*>(Cv) + (size_t)z * (size_t)M * (size_t)ldc + (size_t)row * ldc + col;
+          if (n_vec_ok) *reinterpret_cast<float4*>(C) = make_float4(v[0], v[1], v[2], v[3]);
+          else for (int e = 0; e < 4 && col + e < N; ++e) C[e] = v[e];
+        } else {
+          bf16_t* C = reinterpret_cast<bf16_t*>(Cv) + (size_t)row * ldc + col;
+          for (int e = 0; e < 4 && col + e < N; ++e) {
+            float x = v[e];
+            if constexpr (EPI == EPI_ADD_RES) x += to_f32(R[(size_t)row * ldc + col + e]);
+            C[e] = from_f32<bf16_t>(x);
+          }
         }
       }
     }
+  }
+  if (!has_next) break;
+  vb = vb_next; tm = tm_next; tn = tn_next;
+  // the next tile's first units have landed, this wave's stores are acknowledged and its patch reads are done; the
+  // barrier at the top of the loop publishes all of that before any wave refills slots 3 and 4
+  __builtin_amdgcn_s_waitcnt(0x0070);
   }
 }
 
 static int g_gemm_variant = 1;          // 0: register-staged kernel, 1: direct-to-LDS kernel (default: faster on every shape measured)
 void gemm_set_variant(int v) { g_gemm_variant = v; }
+static int g_gemm_persistent = 1;       // 1: one workgroup per compute unit walks several tiles (see the kernel's tile walk)
+void gemm_set_persistent(int v) { g_gemm_persistent = v; }
+// x extent of the grid for nb tiles: all of them, or one workgroup per compute unit when there are more tiles than units
+static int dl_grid_x(int nb) {
+  static int ncu = -1;
+  if (ncu < 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n = 0;
+    ncu = (n >= 8 && n % 8 == 0) ? n : 0;
+  }
+  return (g_gemm_persistent && ncu > 0 && nb > ncu) ? ncu : nb;
+}
 
 template <int EPI, bool OUT_F32>
 static int launch_dl(hipStream_t st, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int Ksplit, const void* R, int splits) {
@@ -515,7 +559,7 @@ static int launch_dl(hipStream_t st, const void* A, int lda, const void* B, int 
     attr_done = true;
   }
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-  dim3 grid(tiles_m * tiles_n, splits);
+  dim3 grid(splits == 1 ? dl_grid_x(tiles_m * tiles_n) : tiles_m * tiles_n, splits);
   kern<<<grid, 512, DL_LDS_BYTES, st>>>((const bf16_t*)A, lda, (const bf16_t*)B, ldb, C, ldc, M, N, Ksplit, (const bf16_t*)R, tiles_m, tiles_n, 0);
   return 0;
 }
@@ -531,7 +575,7 @@ int k_gemm_swiglu_fwd_mfma(hipStream_t st, const void* X, int ldx, const void* W
     attr_done = true;
   }
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (F + BN / 2 - 1) / (BN / 2);
-  kern<<<dim3(tiles_m * tiles_n, 1), 512, DL_LDS_BYTES, st>>>((const bf16_t*)X, ldx, (const bf16_t*)Wgu, ldw, gu, 2 * F, M, F, K, (const bf16_t*)a, tiles_m, tiles_n, F);
+  kern<<<dim3(dl_grid_x(tiles_m * tiles_n), 1), 512, DL_LDS_BYTES, st>>>((const bf16_t*)X, ldx, (const bf16_t*)Wgu, ldw, gu, 2 * F, M, F, K, (const bf16_t*)a, tiles_m, tiles_n, F);
   return 0;
 }
 
@@ -548,7 +592,7 @@ int k_gemm_swiglu_bwd_mfma(hipStream_t st, const void* G, int ldg, const void* W
     attr_done = true;
   }
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-  kern<<<dim3(tiles_m * tiles_n, 1), 512, DL_LDS_BYTES, st>>>((const bf16_t*)G, ldg, (const bf16_t*)Wd_rows, ldw, dgu_c0, ld2f, M, N, K, (const bf16_t*)gu_c0, tiles_m, tiles_n, half);
+  kern<<<dim3(dl_grid_x(tiles_m * tiles_n), 1), 512, DL_LDS_BYTES, st>>>((const bf16_t*)G, ldg, (const bf16_t*)Wd_rows, ldw, dgu_c0, ld2f, M, N, K, (const bf16_t*)gu_c0, tiles_m, tiles_n, half);
   return 0;
 }
 

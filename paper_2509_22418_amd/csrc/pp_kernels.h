@@ -74,6 +74,7 @@ int k_gemm_swiglu_bwd_mfma(hipStream_t st, const void* G, int ldg, const void* W
 int k_gemm_nt_mfma(hipStream_t st, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
                    int epi, const void* R, int out_f32, int splits, float* partial);
 void gemm_set_variant(int v);          // 0: register-staged MFMA GEMM, 1: direct-to-LDS MFMA GEMM
+void gemm_set_persistent(int v);       // 1 (default): a workgroup per compute unit walks several tiles when there are more tiles than units
 // scratch: 3 * attn_scratch_elems(B, S, h, dh) bf16 elements for the attention-transposed operand copies.
 size_t attn_scratch_elems(int B, int S, int h, int dh);
 int k_attn_fwd_mfma(hipStream_t st, const void* qkv, void* o, float* lse, void* scratch, int B, int S, int h, int dh);

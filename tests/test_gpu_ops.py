@@ -71,6 +71,37 @@ def test_gemm_nt_matches_definition(M, N, K, res, f32, splits, variant):
             assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-4 * scale), (path, np.max(np.abs(got - ref)))
 
 
+@pytest.mark.parametrize("M,N,res", [(4096, 4608, False), (4096, 4352, True), (4200, 4100, True)])
+def test_gemm_with_more_tiles_than_compute_units_walks_tiles_identically(M, N, res):
+    """288 tiles (a multiple of 8: XCD-aware walk), 272 tiles, and 17 x 17 ragged tiles on 256 compute units: some
+    workgroups take two tiles.  Checked against the definition, and bit for bit against one workgroup per tile."""
+    K = 128
+    print(f"case gemm tile walk {M}x{N}x{K} res={res}", flush=True)
+    pp.pp_set_option(None, "gemm_variant", 1)
+    Ad, A = dev_bf16(rnd((M, K), 11))
+    Bd, B = dev_bf16(rnd((N, K), 12))
+    ref = A @ B.T
+    Rd = None
+    if res:
+        Rd, R = dev_bf16(rnd((M, N), 13, std=4.0))
+        ref = ref + R
+    st = torch.cuda.current_stream().cuda_stream
+    out = {}
+    try:
+        for persistent in (1, 0):
+            pp.pp_set_option(None, "gemm_persistent", persistent)
+            Cd = torch.zeros((M, N), dtype=torch.int16, device="cuda")
+            pp.pp_op_gemm_nt(st, pp.PP_BF16, Ad.data_ptr(), K, Bd.data_ptr(), K, Cd.data_ptr(), N, M, N, K,
+                             None if Rd is None else Rd.data_ptr(), 0, 1, None, 0)
+            torch.cuda.synchronize()
+            out[persistent] = Cd.cpu().numpy()
+    finally:
+        pp.pp_set_option(None, "gemm_persistent", 1)
+    got = from_bf16(torch.from_numpy(out[1]))
+    assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-4 * np.sqrt(K))
+    assert np.array_equal(out[0], out[1])
+
+
 def test_gemm_with_leading_dimensions_and_column_slices():
     """Operands and result addressed inside wider matrices (how slices of weights / activations are passed)."""
     M, N, K, lda, ldb, ldc = 384, 320, 256, 512, 640, 1024

@@ -188,6 +188,29 @@ def test_fused_gate_up_activation_matches_stored_projections_and_oracle():
     m.close()
 
 
+def test_fused_swiglu_gemms_with_more_tiles_than_compute_units_match_oracle():
+    """T = 2 x 2304 tokens and d_ff = 4096 give 18 x 32 = 576 tiles in the fused gate/up GEMM and 18 x 16 = 288 in the
+    fused dL/da GEMM: on 256 compute units a workgroup walks several tiles.  Forward values element by element against
+    the oracle's cache, then loss and all gradients (everything trainable)."""
+    cfg = gen.make_config("tiny", n_layers=1, d_model=256, n_heads=2, d_ff=4096, vocab=512, batch=2, seq=2304, dtype="bf16")
+    weights = gen.make_weights(cfg, seed=41)
+    tok, tgt = gen.make_tokens(cfg, seed=41)
+    print("case fused-swiglu tile walk", flush=True)
+    m = make_gpu_model(cfg, weights, dict(all=1))
+    m.step(*m.upload_tokens(tok, tgt), None).item()
+    T, F = tok.size, cfg["d_ff"]
+    _, cache = O.forward(cfg, O.to_f64(weights), tok, tgt)
+    gu = _bf16_to_f32(m.get_raw("dbg.gu.0", (T, 2 * F), np.uint16))
+    a = _bf16_to_f32(m.get_raw("dbg.a.0", (T, F), np.uint16))
+    lc = cache["layers"][0]
+    for name, got, ref in (("g", gu[:, :F], lc["g"]), ("u", gu[:, F:], lc["u"]), ("a", a, lc["a"])):
+        ref = np.asarray(ref).reshape(T, F)
+        assert cosine(got.ravel(), ref.ravel()) >= 0.9995, name
+        assert np.max(np.abs(got - ref)) <= 0.05 * np.max(np.abs(ref)) + 1e-6, name
+    m.close()
+    run_case(cfg, dict(all=1), seed=41)
+
+
 @pytest.mark.parametrize("d_model", [512, 1024, 4096])
 def test_register_resident_rmsnorm_widths_match_oracle(d_model):
     """RMSNorm keeps a row in registers for d = 512, 1024, 2048 and 4096 (one specialisation each; 2048 is the 1.3B

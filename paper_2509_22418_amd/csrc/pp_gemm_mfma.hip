@@ -432,22 +432,22 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
         }
       } else {
         // residual add (or SwiGLU backward): the result is formed in fp32 and rounded once, so the patch holds floats
-        // (32 rows x 256 bytes at a time, 16-byte piece p of row r at p ^ (r & 15)); 16 lanes then cover one 128-byte
-        // row segment of R and of C
+        // (32 rows x 256 bytes at a time, 16-byte piece p of row r at p ^ (r & 15)); 8 lanes then cover one 128-byte
+        // row segment of R and of C with 16-byte accesses
 #pragma unroll
         for (int qt = 0; qt < 4; ++qt) {
           // The saved operands of this quarter (R, and for the SwiGLU backward the second operand ldc2 columns further
-          // on) are requested first, all 8 (16) loads of the wave at once and from clamped addresses so that no branch
+          // on) are requested first, all 4 (8) 16-byte loads of the wave at once and from clamped addresses so that no branch
           // separates them: they travel while the accumulators are turned around in LDS, instead of one dependent
           // load -> compute -> store chain per row group.
-          uint2 rr[8], ru[8];
+          uint4 rr[4], ru[4];
 #pragma unroll
-          for (int it = 0; it < 8; ++it) {
-            const int grow = min(m0 + wm * 128 + qt * 32 + 4 * it + (lane >> 4), M - 1);
-            const int gcol = min(n0 + wn * 64 + (lane & 15) * 4, N - 4);
+          for (int it = 0; it < 4; ++it) {
+            const int grow = min(m0 + wm * 128 + qt * 32 + 8 * it + (lane >> 3), M - 1);
+            const int gcol = min(n0 + wn * 64 + (lane & 7) * 8, N - 8);
             const size_t off = (size_t)grow * ldc + gcol;
-            rr[it] = *reinterpret_cast<const uint2*>(R + off);
-            if constexpr (EPI == EPI_SWIGLU_BWD) ru[it] = *reinterpret_cast<const uint2*>(R + off + ldc2);
+            rr[it] = *reinterpret_cast<const uint4*>(R + off);
+            if constexpr (EPI == EPI_SWIGLU_BWD) ru[it] = *reinterpret_cast<const uint4*>(R + off + ldc2);
           }
 #pragma unroll
           for (int ii = 0; ii < 2; ++ii) {
@@ -460,37 +460,38 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
             }
           }
 #pragma unroll
-          for (int it = 0; it < 8; ++it) {
-            const int row = 4 * it + (lane >> 4), c = lane & 15;
-            const float4 v = *reinterpret_cast<const float4*>(wbase + row * 256 + ((c ^ (row & 15)) << 4));
-            const int grow = m0 + wm * 128 + qt * 32 + row, gcol = n0 + wn * 64 + c * 4;
+          for (int it = 0; it < 4; ++it) {          // a lane takes 8 consecutive columns of a row: 8 lanes cover a 128-byte segment of R and C
+            const int row = 8 * it + (lane >> 3), c = lane & 7;
+            const float4 v0 = *reinterpret_cast<const float4*>(wbase + row * 256 + (((2 * c) ^ (row & 15)) << 4));
+            const float4 v1 = *reinterpret_cast<const float4*>(wbase + row * 256 + (((2 * c + 1) ^ (row & 15)) << 4));
+            const int grow = m0 + wm * 128 + qt * 32 + row, gcol = n0 + wn * 64 + c * 8;
             if (grow < M && gcol < N) {
               const size_t off = (size_t)grow * ldc + gcol;
+              const float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+              const uint32_t rw[4] = {rr[it].x, rr[it].y, rr[it].z, rr[it].w};
               if constexpr (EPI == EPI_SWIGLU_BWD) {
                 // the product is dL/da; R holds the saved gate at this column and the saved up ldc2 columns further on:
                 // dg = da u sig(g) (1 + g (1 - sig(g))) and du = da g sig(g) go to the same two places of C
-                const uint2 rg = rr[it], rv = ru[it];
-                const float da[4] = {v.x, v.y, v.z, v.w};
-                const float gg[4] = {__uint_as_float(rg.x << 16), __uint_as_float(rg.x & 0xffff0000u), __uint_as_float(rg.y << 16), __uint_as_float(rg.y & 0xffff0000u)};
-                const float uu[4] = {__uint_as_float(rv.x << 16), __uint_as_float(rv.x & 0xffff0000u), __uint_as_float(rv.y << 16), __uint_as_float(rv.y & 0xffff0000u)};
-                float dg[4], du[4];
+                const uint32_t uw[4] = {ru[it].x, ru[it].y, ru[it].z, ru[it].w};
+                float dg[8], du[8];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                  const float sg = sigmoid_fast(gg[e]);
-                  du[e] = da[e] * gg[e] * sg;
-                  dg[e] = da[e] * uu[e] * sg * (1.0f + gg[e] * (1.0f - sg));
+                for (int e = 0; e < 8; ++e) {
+                  const float gg = (e & 1) ? __uint_as_float(rw[e >> 1] & 0xffff0000u) : __uint_as_float(rw[e >> 1] << 16);
+                  const float uu = (e & 1) ? __uint_as_float(uw[e >> 1] & 0xffff0000u) : __uint_as_float(uw[e >> 1] << 16);
+                  const float sg = sigmoid_fast(gg);
+                  du[e] = v[e] * gg * sg;
+                  dg[e] = v[e] * uu * sg * (1.0f + gg * (1.0f - sg));
                 }
-                uint2 w;
-                w.x = f32x2_to_bf16x2(dg[0], dg[1]); w.y = f32x2_to_bf16x2(dg[2], dg[3]);
-                *reinterpret_cast<uint2*>(C + off) = w;
-                w.x = f32x2_to_bf16x2(du[0], du[1]); w.y = f32x2_to_bf16x2(du[2], du[3]);
-                *reinterpret_cast<uint2*>(C + off + ldc2) = w;
+                *reinterpret_cast<uint4*>(C + off) = make_uint4(f32x2_to_bf16x2(dg[0], dg[1]), f32x2_to_bf16x2(dg[2], dg[3]),
+                                                                f32x2_to_bf16x2(dg[4], dg[5]), f32x2_to_bf16x2(dg[6], dg[7]));
+                *reinterpret_cast<uint4*>(C + off + ldc2) = make_uint4(f32x2_to_bf16x2(du[0], du[1]), f32x2_to_bf16x2(du[2], du[3]),
+                                                                       f32x2_to_bf16x2(du[4], du[5]), f32x2_to_bf16x2(du[6], du[7]));
               } else {
-                const uint2 r0 = rr[it];
-                uint2 w;
-                w.x = f32x2_to_bf16x2(v.x + __uint_as_float(r0.x << 16), v.y + __uint_as_float(r0.x & 0xffff0000u));
-                w.y = f32x2_to_bf16x2(v.z + __uint_as_float(r0.y << 16), v.w + __uint_as_float(r0.y & 0xffff0000u));
-                *reinterpret_cast<uint2*>(C + off) = w;
+                uint32_t w[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                  w[e] = f32x2_to_bf16x2(v[2 * e] + __uint_as_float(rw[e] << 16), v[2 * e + 1] + __uint_as_float(rw[e] & 0xffff0000u));
+                *reinterpret_cast<uint4*>(C + off) = make_uint4(w[0], w[1], w[2], w[3]);
               }
             }
           }

@@ -4,6 +4,10 @@
 // as stored, input-gradient GEMMs use transposed read-only weight copies, weight-gradient GEMMs use transposed
 // activations with the token dimension as K), so this is the kernel that carries the step's FLOPs.
 //
+// Two kernels share this file: the register-staged one described next (variant 0, kept selectable) and the
+// direct-to-LDS one further down (variant 1, the default; its own comment states what differs: whole-line DMA units,
+// a five-slot ring, 16 x 16 x 32 MFMAs, a tile walk with cross-tile prefetch, fused SwiGLU epilogues).
+//
 // Tiling: 256 x 256 output tile per workgroup of 512 threads = 8 wavefronts (2 per SIMD) arranged 2 (M) x 4 (N);
 // each wavefront owns 128 x 64 = 4 x 2 MFMA tiles of v_mfma_f32_32x32x16_bf16 (128 accumulator registers).
 // K advances in steps of 64: the A and B panels (256 x 64 bf16 each, 32 KB + 32 KB) are staged in LDS, two stages

@@ -45,6 +45,7 @@ def test_query_bytes_and_argument_checks_without_gpu():
     assert lib.pp_query_bytes(ctypes.byref(c), ctypes.byref(badm), 1) == 0 and b"ffn range" in lib.pp_last_error()
     assert lib.pp_local_step(None, None, None, 1, 1, None, None) == -1
     assert lib.pp_outer_delta(None, None, None, None, None, None) == -1
+    assert lib.pp_set_jacobian_slices(None, 1, 0, 0) == -1
 
 
 def test_recompute_shrinks_the_activation_plan_without_gpu():

@@ -282,6 +282,10 @@ def main():
     roofline = dict(bound="mfma", kernel="gemm_nt_mfma_dl_kernel (all forward / dX / dW GEMM launches of the step)",
                     achieved=mr["gemm_tflops"], peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
                     frac=round(mr["gemm_tflops"] / PEAK_BF16_TFLOPS, 4) if mr["gemm_tflops"] else None, traffic=None,
+                    traffic_note="null on purpose: FETCH_SIZE / WRITE_SIZE sit between L2 and the fabric, so for a GEMM they count "
+                                 "L2 fills served by the Infinity Cache as well (about 0.9 GB per launch on average against 0.13-0.27 GB "
+                                 "of operands, profiles/hbm_traffic_1p3b_rho32_pmc.txt), not HBM bytes; for the HBM-bound kernels of "
+                                 "the step the same counters equal the algorithmic bytes within 1-2 %",
                     avg_launch_ms=round(gemm_ms_launch, 4), launches_per_step=mr["gemm_launches_per_step"],
                     gemm_share_of_step_time=round(mr["gemm_ms_per_step"] / mr["ms_per_step"], 3))
     cpu = None

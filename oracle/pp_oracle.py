@@ -24,16 +24,19 @@ What it computes (paper: "Partial Parameter Updates", Algorithm 1 and Section 2.
                          weight decay either).
   * outer_step():        Alg. 1's delta, count normalisation and OuterOpt (Nesterov-momentum SGD,
                          Experimental Setup) for the node's own trainable subset.
-  * flops_closed_form / paper_flops: closed forms for executed matmul FLOPs.
+  * flops_forward / flops_backward_ffn_slice / flops_backward_all: closed forms for the matmul
+                         FLOPs the step executes;  paper_flops: the paper's own closed forms.
 
 Architecture details the paper leaves open follow the benchmark configs: pre-norm RMSNorm
 (eps inside the square root), rotary embeddings with half-split pairing (i, i+dh/2) and angle
 pos * base^(-2i/dh), causal attention, SwiGLU FFN  y = (silu(x Wg^T) * (x Wu^T)) Wd  with
 Wg, Wu, Wd all stored (d_ff x d_model), untied embedding / lm_head, no biases, no dropout.
 
-Pins (tests/test_oracle_*.py): central finite differences for every tensor; library routines
+Pins (tests/test_oracle_pins.py): central finite differences for every tensor; library routines
 (rms_norm, scaled-dot-product attention, cross entropy, AdamW, Nesterov SGD) on the cases that
-reduce to them; closed forms (rotary, AdamW step 1, Nesterov step 1, loss ~ ln V at init);
+reduce to them; LocalTrainer as a whole (decay_mask_for and the packed order included) against
+library autograd + library AdamW with decayed / undecayed parameter groups; its bf16-storage mode
+against the library's bf16 cast; closed forms (rotary, AdamW step 1, Nesterov step 1, loss ~ ln V at init);
 invariants (causality, slice additivity of the FFN, masked == slice of full, frozen unchanged);
 the detach ablation against library autograd with the dropped units' activations detached;
 FLOP counter == closed form; the paper's FLOP formulas reproduce its "15% fewer FLOPs" and its

@@ -454,3 +454,100 @@ def test_definition_and_restricted_paths_give_same_training_trajectory():
         assert abs(la - lb) < 1e-12
     for k in a.params:
         np.testing.assert_allclose(a.params[k], b.params[k], rtol=1e-9, atol=1e-12)
+
+
+# ------------------------------------------------------------------ the trainer as a whole: library autograd + library AdamW
+def _leaf_params(cfg, params, mask):
+    """torch leaves for a mask: every whole trainable tensor is one leaf; a sliced FFN tensor is three row blocks
+    (below / trainable / above) of which only the middle one is a leaf that the optimizer sees.  Returns
+    (tensors for the model, decayed leaves, undecayed leaves, readers name -> callable giving the full array)."""
+    fl, fh = mask["ffn_lo"], mask["ffn_hi"]
+    hl, hh = mask["head_lo"], mask["head_hi"]
+    d, dh = cfg["d_model"], cfg["d_model"] // cfg["n_heads"]
+    model, decay, no_decay = {}, [], []
+    for name, w in params.items():
+        kind = name.split(".")[-1]
+        t = lambda a, rg: torch.tensor(np.array(a), dtype=torch.float64, requires_grad=rg)
+        if kind in ("wg", "wu", "wd") and fh > fl:
+            lo, mid, hi = t(w[:fl], False), t(w[fl:fh], True), t(w[fh:], False)
+            decay.append(mid)
+            model[name] = (lo, mid, hi)
+        elif kind == "wqkv" and hh > hl:
+            blocks = []
+            for blk in range(3):
+                r0, r1 = blk * d + hl * dh, blk * d + hh * dh
+                a, b, c = t(w[blk * d:r0], False), t(w[r0:r1], True), t(w[r1:(blk + 1) * d], False)
+                decay.append(b)
+                blocks += [a, b, c]
+            model[name] = tuple(blocks)
+        else:
+            flag = {"embed": "train_embed", "lm_head": "train_lm_head", "wo": "train_wo"}.get(kind, "train_norms" if kind.endswith("norm") else None)
+            leaf = t(w, bool(flag and mask.get(flag)))
+            if leaf.requires_grad:
+                (no_decay if kind.endswith("norm") else decay).append(leaf)
+            model[name] = (leaf,)
+    return model, decay, no_decay
+
+
+@pytest.mark.parametrize("mname", ["all", "paper_mlp", "paper_mlp_heads", "ffn_slice"])
+def test_local_trainer_matches_library_autograd_with_adamw_parameter_groups(mname):
+    """Three inner steps of Alg. 1 by the oracle's LocalTrainer against library autograd + library AdamW with two
+    parameter groups (matrices decayed, norm gains not).  The norm gains sit between the matrices in the packed order,
+    so a decay vector that is misaligned with that order, or that decays the gains, moves parameters differently; the
+    frozen row blocks are not leaves of the library optimizer at all, so they must stay exactly as they were."""
+    cfg = small_cfg(n_layers=2)
+    params, _, _ = setup(cfg)
+    mask = MASKS[mname](cfg)
+    model, decay, no_decay = _leaf_params(cfg, params, mask)
+    hp = dict(HP, lr=3e-3, weight_decay=0.3)          # decay large enough that a wrong decay flag shows at once
+    groups = [dict(params=decay, weight_decay=hp["weight_decay"])]
+    if no_decay:
+        groups.append(dict(params=no_decay, weight_decay=0.0))
+    opt = torch.optim.AdamW(groups, lr=hp["lr"], betas=(hp["beta1"], hp["beta2"]), eps=hp["eps"])
+    tr = O.LocalTrainer(cfg, params, mask)
+    assert tr.decay.size == tr.master.size
+    n_gain_elems = sum(x.numel() for x in no_decay)
+    assert int((tr.decay == 0).sum()) == n_gain_elems and int((tr.decay == 1).sum()) == tr.master.size - n_gain_elems
+    for step in range(3):
+        tok, tgt = gen.make_tokens(cfg, 17, step=step)
+        loss_o, _ = tr.step(tok, tgt, hp, restricted=(step == 1))
+        opt.zero_grad()
+        tparams = {k: (v[0] if len(v) == 1 else torch.cat(v, dim=0)) for k, v in model.items()}
+        loss_t = _autograd_model_loss(cfg, tparams, tok, tgt, [(0, cfg["d_ff"])])
+        assert abs(float(loss_t.detach()) - loss_o) <= 1e-11 * abs(loss_o), step
+        loss_t.backward()
+        opt.step()
+    for k, v in model.items():
+        now = (v[0] if len(v) == 1 else torch.cat(v, dim=0)).detach().numpy()
+        np.testing.assert_allclose(tr.params[k], now, rtol=1e-8, atol=1e-11, err_msg=k)
+
+
+def test_local_trainer_bf16_storage_keeps_master_and_rounds_compute_copy_like_the_library():
+    """Mixed precision of the Memory Usage paragraph (full-precision master, bf16 compute copy): after a step with
+    storage='bf16' the master equals the full-precision trainer's master (same start, same gradient), the trainable
+    rows of the parameters are the library's round-to-nearest-even bf16 cast of that master, and frozen rows are untouched."""
+    cfg = small_cfg()
+    params = O.to_f64(gen.make_weights(dict(cfg, dtype="bf16"), seed=8, std=0.2))
+    mask = gen.paper_mlp_mask(cfg, node=1, n_slices=4)
+    tok, tgt = gen.make_tokens(cfg, 8)
+    a = O.LocalTrainer(cfg, params, mask)
+    b = O.LocalTrainer(cfg, params, mask, storage="bf16")
+    la, ga = a.step(tok, tgt, HP)
+    lb, gb = b.step(tok, tgt, HP)
+    assert la == lb and np.array_equal(ga, gb)
+    np.testing.assert_array_equal(a.master, b.master)
+    want = torch.tensor(b.master, dtype=torch.float64).to(torch.float32).to(torch.bfloat16).to(torch.float64).numpy()
+    got = O.pack(b.params, b.segs)
+    np.testing.assert_array_equal(got, want)
+    assert np.any(got != b.master)                       # the compute copy really is coarser than the master
+    np.testing.assert_array_equal(O.pack(a.params, a.segs), a.master)
+    fl, fh = mask["ffn_lo"], mask["ffn_hi"]
+    keep = np.ones(cfg["d_ff"], bool)
+    keep[fl:fh] = False
+    for l in range(cfg["n_layers"]):
+        for nm in ("wg", "wu", "wd"):
+            k = f"layers.{l}.{nm}"
+            assert np.array_equal(b.params[k][keep], params[k][keep])
+    # the next step starts from the rounded copy: its loss differs from the full-precision trainer's
+    tok2, tgt2 = gen.make_tokens(cfg, 8, step=1)
+    assert a.step(tok2, tgt2, HP)[0] != b.step(tok2, tgt2, HP)[0]

@@ -91,7 +91,8 @@ typedef struct { float lr, momentum; int32_t nesterov; float m_count; } pp_outer
 size_t pp_query_bytes(const pp_config* cfg, const pp_mask* mask, int which);
 
 /* Creates a handle over caller-owned buffers (256-byte aligned, at least the queried sizes).
- * params_dev content is taken as is (upload with pp_set_tensor, then the shadows are refreshed by it).
+ * params_dev content is taken as is: fill it with pp_set_tensor, or directly (device copy, checkpoint load) in the canonical
+ * layout BEFORE pp_set_trainable_mask, which forms the transposed read-only copies of all matrices from it.
  * hip_stream: a hipStream_t (NULL = default stream).  Blocks until its one-time tables are built. */
 int pp_init_model(const pp_config* cfg, void* params_dev, size_t params_bytes, void* workspace_dev,
                   size_t workspace_bytes, void* hip_stream, pp_model** out);
@@ -111,7 +112,8 @@ int pp_get_tensor(pp_model* m, const char* name, void* host_dst, size_t bytes);
 /* Fixes I_train (it stays fixed during local training, Section 2.2), packs the trainable rows into
  * state_dev in network order (embed, then per layer attn_norm, wqkv q/k/v head rows, wo, ffn_norm, wg,
  * wu, wd rows, then final_norm, lm_head), snapshots fp32 masters from the current weights, zeroes m and v
- * and resets the step counter.  May be called again (new round, or new mask). */
+ * and resets the step counter; also rebuilds the transposed weight copies in the workspace from params_dev.
+ * May be called again (new round, new mask, or after params_dev was rewritten by the caller). */
 int pp_set_trainable_mask(pp_model* m, const pp_mask* mask, void* state_dev, size_t state_bytes);
 
 /* One local step (Algorithm 1, inner loop body): forward over all parameters, restricted backward,
@@ -160,11 +162,18 @@ int pp_synth_delta_sum(pp_model* m, float* dst_dev, size_t n, const uint64_t* ke
  * bytes moved, and the number of trainable elements. */
 int pp_get_counters(pp_model* m, double* flops_fwd, double* flops_bwd, double* adamw_bytes, int64_t* n_trainable);
 
+/* How many contractions (GEMM calls incl. their split-K reduction, attention forward / backward calls) of the most recent
+ * pp_local_step ran on the matrix-core (MFMA) kernels and how many on the plain fp32-FMA kernels.  With PP_F32 storage all
+ * are plain by design; with PP_BF16 a plain call means a shape or alignment the MFMA kernels do not take (or "force_plain"):
+ * the result is still correct, only slow -- tests of the bf16 benchmark shapes assert plain_calls == 0. */
+int pp_get_launch_counts(pp_model* m, int64_t* matrix_core_calls, int64_t* plain_calls);
+
 /* Options for tests and profiling.  "force_plain": 0 = automatic (MFMA kernels when shapes allow), 1 = force the
  * plain (non-MFMA) kernels.  "time_gemm": 1 = bracket every GEMM launch of later pp_local_step calls with a pair
  * of HIP events on the model's stream (host-side events only; no device memory), 0 = off; setting it resets the totals.
- * "gemm_variant" (process-wide; m may be NULL): 1 = direct-to-LDS MFMA GEMM (default), 0 = register-staged MFMA GEMM.
- * "gemm_persistent" (process-wide; m may be NULL): 1 (default) = when a GEMM has more tiles than the GPU has compute
+ * "gemm_variant" (process-wide, for tests and A/B timing only; m may be NULL; takes effect for launches issued after the
+ * call returns, on any thread): 1 = direct-to-LDS MFMA GEMM (default), 0 = register-staged MFMA GEMM.
+ * "gemm_persistent" (process-wide, same caveats; m may be NULL): 1 (default) = when a GEMM has more tiles than the GPU has compute
  * units, one workgroup per unit walks several tiles and requests its next tile's first operands before the current
  * tile's epilogue; 0 = one workgroup per tile.  Same results bit for bit. */
 int pp_set_option(pp_model* m, const char* key, int64_t value);

@@ -14,7 +14,7 @@ import numpy as np
 PP_F32, PP_BF16 = 0, 1
 PP_BYTES_PARAMS, PP_BYTES_STATE, PP_BYTES_WORKSPACE, PP_BYTES_SHADOW, PP_BYTES_ACTIVATIONS = range(5)
 EXPORTS = ["pp_query_bytes", "pp_init_model", "pp_set_tensor", "pp_get_tensor", "pp_set_trainable_mask", "pp_local_step",
-           "pp_set_jacobian_slices", "pp_outer_delta", "pp_outer_delta_group", "pp_synth_delta_sum", "pp_get_counters", "pp_get_gemm_timing", "pp_set_option", "pp_last_error", "pp_free",
+           "pp_set_jacobian_slices", "pp_outer_delta", "pp_outer_delta_group", "pp_synth_delta_sum", "pp_get_counters", "pp_get_launch_counts", "pp_get_gemm_timing", "pp_set_option", "pp_last_error", "pp_free",
            "pp_op_gemm_nt", "pp_op_attention_fwd", "pp_op_attention_bwd"]
 
 
@@ -81,6 +81,8 @@ def load_library():
     lib.pp_synth_delta_sum.argtypes = [vp, vp, sz, C.POINTER(C.c_uint64), i32, C.c_float]
     lib.pp_get_counters.restype = C.c_int
     lib.pp_get_counters.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(i64)]
+    lib.pp_get_launch_counts.restype = C.c_int
+    lib.pp_get_launch_counts.argtypes = [vp, C.POINTER(i64), C.POINTER(i64)]
     lib.pp_get_gemm_timing.restype = C.c_int
     lib.pp_get_gemm_timing.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(i64)]
     lib.pp_set_option.restype = C.c_int
@@ -168,6 +170,12 @@ def pp_get_counters(h):
     f, b, a, n = C.c_double(), C.c_double(), C.c_double(), C.c_int64()
     _check(load_library().pp_get_counters(h, C.byref(f), C.byref(b), C.byref(a), C.byref(n)), "pp_get_counters")
     return dict(flops_fwd=f.value, flops_bwd=b.value, adamw_bytes=a.value, n_trainable=n.value)
+
+
+def pp_get_launch_counts(h):
+    a, b = C.c_int64(), C.c_int64()
+    _check(load_library().pp_get_launch_counts(h, C.byref(a), C.byref(b)), "pp_get_launch_counts")
+    return dict(matrix_core_calls=a.value, plain_calls=b.value)
 
 
 def pp_get_gemm_timing(h):
@@ -303,6 +311,9 @@ class LocalStepModel:
 
     def counters(self):
         return pp_get_counters(self.h)
+
+    def launch_counts(self):
+        return pp_get_launch_counts(self.h)
 
     def set_option(self, key: str, value: int):
         pp_set_option(self.h, key, value)

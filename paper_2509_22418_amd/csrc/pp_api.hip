@@ -165,6 +165,7 @@ struct pp_model {
   int force_plain = 0;
   int jac_mode = 0, jac_lo = 0, jac_hi = 0;          // ablation: FFN input Jacobian over the trainable slice (+ units jac_lo..jac_hi-1) only
   double flops_fwd = 0, flops_bwd = 0, flops_recompute = 0, adamw_bytes = 0;
+  int64_t n_mfma = 0, n_plain = 0;          // contractions (GEMM / attention calls) of the last step by kernel family
   double* flop_acc = nullptr;
   // optional GEMM timing: one event pair per GEMM launch, summed by pp_get_gemm_timing
   int time_gemm = 0;
@@ -204,7 +205,9 @@ static int check_cfg(const pp_config* c) {
   const int dh = c->d_model / c->n_heads;
   if (dh % 2 || dh > 256) return fail(PP_EINVAL, "config: head dim must be even and <= 256");
   if (c->d_model % 8 || c->d_ff % 8 || c->vocab % 8) return fail(PP_EINVAL, "config: d_model, d_ff and vocab must be multiples of 8");
-  if ((size_t)c->vocab * (c->dtype == PP_F32 ? 4 : 2) > 64 * 1024 - 256) return fail(PP_EINVAL, "config: vocab row does not fit the cross-entropy LDS stage");
+  if (!ce_row_fits(c->dtype, c->vocab))
+    return fail(PP_EINVAL, c->dtype == PP_BF16 ? "config: vocab > 65536 is not supported by the cross-entropy kernels (bf16)"
+                                               : "config: vocab row does not fit the cross-entropy LDS stage (fp32: vocab <= 16320)");
   if (c->max_seq > 8192) return fail(PP_EINVAL, "config: max_seq > 8192 not supported");
   if ((double)c->max_batch * c->max_seq > 1e8) return fail(PP_EINVAL, "config: max_batch*max_seq too large");
   if (!(c->rms_eps > 0.f) || !(c->rope_base > 1.f)) return fail(PP_EINVAL, "config: rms_eps must be > 0 and rope_base > 1");
@@ -432,6 +435,27 @@ extern "C" int pp_get_tensor(pp_model* m, const char* name, void* host_dst, size
 }
 
 // ------------------------------------------------------------------------------------------------ mask / state
+// Every transposed read-only weight copy is formed again from the canonical parameter buffer (one transpose per matrix).
+static void rebuild_shadows(pp_model* m) {
+  const pp_config& c = m->cfg;
+  const Layout& L = m->lay;
+  const size_t es = esize(c);
+  const int d = c.d_model, F = c.d_ff, V = c.vocab;
+  char* sh = m->wsp + m->ws.shadow;
+  auto tr = [&](int64_t off, int rows, int cols, int64_t sh_off, int sh_ld) {
+    k_transpose(m->st, c.dtype, m->params + off * es, cols, sh + sh_off * es, sh_ld, rows, cols);
+  };
+  for (int l = 0; l < c.n_layers; ++l) {
+    const int64_t lb = L.layer0 + l * L.layer_stride, sb = L.sh_layer0 + l * L.sh_layer_stride;
+    tr(lb + L.o_wqkv, 3 * d, d, sb + L.sh_wqkv, 3 * d);
+    tr(lb + L.o_wo, d, d, sb + L.sh_wo, d);
+    tr(lb + L.o_wg, F, d, sb + L.sh_wgu, 2 * F);
+    tr(lb + L.o_wu, F, d, sb + L.sh_wgu + F, 2 * F);
+    tr(lb + L.o_wd, F, d, sb + L.sh_wd, F);
+  }
+  tr(L.lm_head, V, d, L.sh_lm_head, V);
+}
+
 extern "C" int pp_set_trainable_mask(pp_model* m, const pp_mask* mask, void* state_dev, size_t state_bytes) {
   if (!m) return fail(PP_EINVAL, "pp_set_trainable_mask: NULL model");
   if (int rc = check_mask(&m->cfg, mask)) return rc;
@@ -464,6 +488,7 @@ extern "C" int pp_set_trainable_mask(pp_model* m, const pp_mask* mask, void* sta
   m->n_shadow_segs = (int)ssegs.size(); m->n_shadow_tiles = tiles; m->shadow_vec_ok = vec_ok;
   char* sb = (char*)state_dev;
   m->sp = (float*)sb; m->sm = (float*)(sb + quarter); m->sv = (float*)(sb + 2 * quarter); m->sg = (float*)(sb + 3 * quarter);
+  rebuild_shadows(m);          // the parameter buffer may have been filled without pp_set_tensor (device copy, checkpoint load)
   k_pack_master(m->st, m->cfg.dtype, m->params, (const RowInfo*)(m->wsp + plan.rows), m->sp, m->n_rows, d);
   k_fill_f32(m->st, m->sm, (size_t)n, 0.f);
   k_fill_f32(m->st, m->sv, (size_t)n, 0.f);
@@ -480,7 +505,8 @@ static void gemm_nt(pp_model* m, const void* A, int lda, const void* B, int ldb,
   if (m->flop_acc) *m->flop_acc += 2.0 * M * N * K;
   GemmTimer timer(m, 2.0 * M * N * K);
   if (m->cfg.dtype == PP_BF16 && !m->force_plain &&
-      k_gemm_nt_mfma(m->st, A, lda, B, ldb, C, ldc, M, N, K, epi, R, 0, 1, nullptr) == 0) return;
+      k_gemm_nt_mfma(m->st, A, lda, B, ldb, C, ldc, M, N, K, epi, R, 0, 1, nullptr) == 0) { m->n_mfma++; return; }
+  m->n_plain++;
   k_gemm_nt_plain(m->st, m->cfg.dtype, A, lda, B, ldb, C, ldc, M, N, K, epi, R, 0);
 }
 
@@ -490,6 +516,7 @@ static bool gemm_swiglu(pp_model* m, const void* X, const void* Wgu, void* gu, v
   GemmTimer timer(m, 2.0 * T * (2.0 * F) * d);
   if (k_gemm_swiglu_fwd_mfma(m->st, X, d, Wgu, d, gu, a, T, F, d) != 0) { timer.cancel(); return false; }
   if (m->flop_acc) *m->flop_acc += 2.0 * T * (2.0 * F) * d;
+  m->n_mfma++;
   return true;
 }
 
@@ -499,6 +526,7 @@ static bool gemm_swiglu_bwd(pp_model* m, const void* G, const void* Wd_rows, con
   GemmTimer timer(m, 2.0 * T * (double)nc * d);
   if (k_gemm_swiglu_bwd_mfma(m->st, G, d, Wd_rows, d, gu_c0, dgu_c0, 2 * F, F, T, nc, d) != 0) { timer.cancel(); return false; }
   if (m->flop_acc) *m->flop_acc += 2.0 * T * (double)nc * d;
+  m->n_mfma++;
   return true;
 }
 
@@ -516,8 +544,10 @@ static void gemm_dw(pp_model* m, const void* At, const void* Bt, float* G, int M
   if (m->cfg.dtype == PP_BF16 && !m->force_plain &&
       k_gemm_nt_mfma(m->st, At, K, Bt, K, G, N, M, N, K, EPI_STORE, nullptr, 1, splits, partial) == 0) {
     if (splits > 1) k_splitk_reduce(m->st, partial, G, N, M, N, splits);
+    m->n_mfma++;
     return;
   }
+  m->n_plain++;
   if (splits == 1) { k_gemm_nt_plain(m->st, m->cfg.dtype, At, K, Bt, K, G, N, M, N, K, EPI_STORE, nullptr, 1); return; }
   k_gemm_nt_plain_splitk(m->st, m->cfg.dtype, At, K, Bt, K, partial, M, N, K, splits);
   k_splitk_reduce(m->st, partial, G, N, M, N, splits);
@@ -526,7 +556,8 @@ static void gemm_dw(pp_model* m, const void* At, const void* Bt, float* G, int M
 static void attn_fwd(pp_model* m, const void* qkv, void* o, float* lse, int B, int S) {
   const int h = m->cfg.n_heads, dh = m->cfg.d_model / h;
   if (m->flop_acc) *m->flop_acc += 4.0 * ((double)B * S * (S + 1) / 2) * m->cfg.d_model;
-  if (m->cfg.dtype == PP_BF16 && !m->force_plain && k_attn_fwd_mfma(m->st, qkv, o, lse, m->wsp + m->ws.at, B, S, h, dh) == 0) return;
+  if (m->cfg.dtype == PP_BF16 && !m->force_plain && k_attn_fwd_mfma(m->st, qkv, o, lse, m->wsp + m->ws.at, B, S, h, dh) == 0) { m->n_mfma++; return; }
+  m->n_plain++;
   k_attn_fwd_plain(m->st, m->cfg.dtype, qkv, o, lse, B, S, h, dh);
 }
 // attention backward followed by the rotary embedding's backward on dq, dk (fused into the MFMA kernels' epilogues)
@@ -535,7 +566,8 @@ static void attn_bwd(pp_model* m, const void* qkv, const void* o, const float* l
   const int h = m->cfg.n_heads, dh = m->cfg.d_model / h;
   if (m->flop_acc) *m->flop_acc += 8.0 * ((double)B * S * (S + 1) / 2) * m->cfg.d_model;
   if (m->cfg.dtype == PP_BF16 && !m->force_plain &&
-      k_attn_bwd_mfma(m->st, qkv, o, lse, dO, dqkv, Dbuf, m->wsp + m->ws.at, B, S, h, dh, cosb, sinb) == 0) return;
+      k_attn_bwd_mfma(m->st, qkv, o, lse, dO, dqkv, Dbuf, m->wsp + m->ws.at, B, S, h, dh, cosb, sinb) == 0) { m->n_mfma++; return; }
+  m->n_plain++;
   k_attn_bwd_plain(m->st, m->cfg.dtype, qkv, o, lse, dO, dqkv, Dbuf, B, S, h, dh);
   k_rope(m->st, m->cfg.dtype, dqkv, cosb, sinb, B, S, h, dh, 1);
 }
@@ -574,6 +606,7 @@ extern "C" int pp_local_step(pp_model* m, const int32_t* tokens_dev, const int32
 
   // ---------------- forward over all parameters (Section 2.2: "the forward pass is standard")
   m->flops_fwd = 0; m->flops_bwd = 0; m->flops_recompute = 0;
+  m->n_mfma = 0; m->n_plain = 0;
   m->flop_acc = &m->flops_fwd;
   k_embed(st, dt, tokens_dev, canon(ly.embed), act(0, w.a_x), T, d, V);
   // one layer forward; xnext == nullptr: stop after the SwiGLU product (all that a recomputation needs)
@@ -813,6 +846,13 @@ extern "C" int pp_get_counters(pp_model* m, double* flops_fwd, double* flops_bwd
   if (flops_bwd) *flops_bwd = m->flops_bwd;
   if (adamw_bytes) *adamw_bytes = m->adamw_bytes;
   if (n_trainable) *n_trainable = m->n_train;
+  return PP_OK;
+}
+
+extern "C" int pp_get_launch_counts(pp_model* m, int64_t* matrix_core_calls, int64_t* plain_calls) {
+  if (!m) return fail(PP_EINVAL, "pp_get_launch_counts: NULL model");
+  if (matrix_core_calls) *matrix_core_calls = m->n_mfma;
+  if (plain_calls) *plain_calls = m->n_plain;
   return PP_OK;
 }
 

@@ -21,6 +21,9 @@
 #include "pp_kernels.h"
 #include "pp_dev.h"
 
+#include <atomic>
+#include <mutex>
+
 namespace pp {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -540,29 +543,35 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
   }
 }
 
-static int g_gemm_variant = 1;          // 0: register-staged kernel, 1: direct-to-LDS kernel (default: faster on every shape measured)
-void gemm_set_variant(int v) { g_gemm_variant = v; }
-static int g_gemm_persistent = 1;       // 1: one workgroup per compute unit walks several tiles (see the kernel's tile walk)
-void gemm_set_persistent(int v) { g_gemm_persistent = v; }
+// Process-wide test / A-B switches (relaxed atomics: a launch sees the value of the last completed setter call).
+static std::atomic<int> g_gemm_variant{1};          // 0: register-staged kernel, 1: direct-to-LDS kernel (default: faster on every shape measured)
+void gemm_set_variant(int v) { g_gemm_variant.store(v, std::memory_order_relaxed); }
+static std::atomic<int> g_gemm_persistent{1};       // 1: one workgroup per compute unit walks several tiles (see the kernel's tile walk)
+void gemm_set_persistent(int v) { g_gemm_persistent.store(v, std::memory_order_relaxed); }
+// One-time opt-in of a kernel to more than 64 KB of dynamic LDS; safe when several host threads launch concurrently.
+struct LdsOptIn {
+  std::once_flag once;
+  bool ok = false;
+  bool operator()(const void* kern, int bytes) {
+    std::call_once(once, [&] { ok = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) == hipSuccess; });
+    return ok;
+  }
+};
 // x extent of the grid for nb tiles: all of them, or one workgroup per compute unit when there are more tiles than units
 static int dl_grid_x(int nb) {
-  static int ncu = -1;
-  if (ncu < 0) {
+  static const int ncu = [] {
     int dev = 0, n = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n = 0;
-    ncu = (n >= 8 && n % 8 == 0) ? n : 0;
-  }
-  return (g_gemm_persistent && ncu > 0 && nb > ncu) ? ncu : nb;
+    return (n >= 8 && n % 8 == 0) ? n : 0;
+  }();
+  return (g_gemm_persistent.load(std::memory_order_relaxed) && ncu > 0 && nb > ncu) ? ncu : nb;
 }
 
 template <int EPI, bool OUT_F32>
 static int launch_dl(hipStream_t st, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int Ksplit, const void* R, int splits) {
-  static bool attr_done = false;
+  static LdsOptIn opt_in;
   auto kern = gemm_nt_mfma_dl_kernel<EPI, OUT_F32>;
-  if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, DL_LDS_BYTES) != hipSuccess) return 1;
-    attr_done = true;
-  }
+  if (!opt_in(reinterpret_cast<const void*>(kern), DL_LDS_BYTES)) return 1;
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   dim3 grid(splits == 1 ? dl_grid_x(tiles_m * tiles_n) : tiles_m * tiles_n, splits);
   kern<<<grid, 512, DL_LDS_BYTES, st>>>((const bf16_t*)A, lda, (const bf16_t*)B, ldb, C, ldc, M, N, Ksplit, (const bf16_t*)R, tiles_m, tiles_n, 0);
@@ -571,14 +580,11 @@ static int launch_dl(hipStream_t st, const void* A, int lda, const void* B, int 
 
 // gu[M x 2F] (ld 2F) = X[M x K] [Wg; Wu]^T and a[M x F] = silu(gate) * up in one launch; Wgu = the 2F x K stack
 int k_gemm_swiglu_fwd_mfma(hipStream_t st, const void* X, int ldx, const void* Wgu, int ldw, void* gu, void* a, int M, int F, int K) {
-  if (g_gemm_variant != 1 || M < 1 || F < 8 || (F & 7) || K < DL_BK || K % DL_BK || (ldx & 7) || (ldw & 7)) return 1;
+  if (g_gemm_variant.load(std::memory_order_relaxed) != 1 || M < 1 || F < 8 || (F & 7) || K < DL_BK || K % DL_BK || (ldx & 7) || (ldw & 7)) return 1;
   if (((uintptr_t)X | (uintptr_t)Wgu | (uintptr_t)gu | (uintptr_t)a) & 15) return 1;
-  static bool attr_done = false;
+  static LdsOptIn opt_in;
   auto kern = gemm_nt_mfma_dl_kernel<EPI_SWIGLU, false>;
-  if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, DL_LDS_BYTES) != hipSuccess) return 1;
-    attr_done = true;
-  }
+  if (!opt_in(reinterpret_cast<const void*>(kern), DL_LDS_BYTES)) return 1;
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (F + BN / 2 - 1) / (BN / 2);
   kern<<<dim3(dl_grid_x(tiles_m * tiles_n), 1), 512, DL_LDS_BYTES, st>>>((const bf16_t*)X, ldx, (const bf16_t*)Wgu, ldw, gu, 2 * F, M, F, K, (const bf16_t*)a, tiles_m, tiles_n, F);
   return 0;
@@ -588,14 +594,11 @@ int k_gemm_swiglu_fwd_mfma(hipStream_t st, const void* X, int ldx, const void* W
 // with leading dimension ld2f = 2F; N = number of hidden units (rows of Wd_rows), half = F
 int k_gemm_swiglu_bwd_mfma(hipStream_t st, const void* G, int ldg, const void* Wd_rows, int ldw, const void* gu_c0, void* dgu_c0, int ld2f, int half,
                            int M, int N, int K) {
-  if (g_gemm_variant != 1 || M < 1 || N < 8 || (N & 7) || (ld2f & 7) || (half & 7) || K < DL_BK || K % DL_BK || (ldg & 7) || (ldw & 7)) return 1;
+  if (g_gemm_variant.load(std::memory_order_relaxed) != 1 || M < 1 || N < 8 || (N & 7) || (ld2f & 7) || (half & 7) || K < DL_BK || K % DL_BK || (ldg & 7) || (ldw & 7)) return 1;
   if (((uintptr_t)G | (uintptr_t)Wd_rows | (uintptr_t)gu_c0 | (uintptr_t)dgu_c0) & 15) return 1;
-  static bool attr_done = false;
+  static LdsOptIn opt_in;
   auto kern = gemm_nt_mfma_dl_kernel<EPI_SWIGLU_BWD, false>;
-  if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, DL_LDS_BYTES) != hipSuccess) return 1;
-    attr_done = true;
-  }
+  if (!opt_in(reinterpret_cast<const void*>(kern), DL_LDS_BYTES)) return 1;
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   kern<<<dim3(dl_grid_x(tiles_m * tiles_n), 1), 512, DL_LDS_BYTES, st>>>((const bf16_t*)G, ldg, (const bf16_t*)Wd_rows, ldw, dgu_c0, ld2f, M, N, K, (const bf16_t*)gu_c0, tiles_m, tiles_n, half);
   return 0;
@@ -603,13 +606,10 @@ int k_gemm_swiglu_bwd_mfma(hipStream_t st, const void* G, int ldg, const void* W
 
 template <int EPI, bool OUT_F32>
 static int launch(hipStream_t st, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int Ksplit, const void* R, int splits) {
-  static bool attr_done = false;          // one-time opt-in to > 64 KB of dynamic LDS for this instantiation
+  static LdsOptIn opt_in;          // one-time opt-in to > 64 KB of dynamic LDS for this instantiation
   auto kern = gemm_nt_mfma_kernel<EPI, OUT_F32>;
-  if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES) != hipSuccess) return 1;
-    attr_done = true;
-  }
-  if (g_gemm_variant == 1) return launch_dl<EPI, OUT_F32>(st, A, lda, B, ldb, C, ldc, M, N, Ksplit, R, splits);
+  if (!opt_in(reinterpret_cast<const void*>(kern), GEMM_LDS_BYTES)) return 1;
+  if (g_gemm_variant.load(std::memory_order_relaxed) == 1) return launch_dl<EPI, OUT_F32>(st, A, lda, B, ldb, C, ldc, M, N, Ksplit, R, splits);
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   dim3 grid(tiles_m * tiles_n, splits);
   kern<<<grid, 512, GEMM_LDS_BYTES, st>>>((const bf16_t*)A, lda, (const bf16_t*)B, ldb, C, ldc, M, N, Ksplit, (const bf16_t*)R, tiles_m, tiles_n);

@@ -36,6 +36,9 @@ void k_swiglu_fwd(hipStream_t st, int dtype, const void* gu, void* a, int T, int
 void k_swiglu_bwd(hipStream_t st, int dtype, const void* gu, const void* dA, int ldA, void* dgu, int T, int F, int c0, int c1);
 void k_count_valid(hipStream_t st, const int32_t* targets, int T, int V, int32_t* n_valid);
 // logits [T x V] are overwritten with dL/dlogits; rowloss[T] gets the per-row loss (0 on ignored rows)
+// whether k_cross_entropy has a kernel for rows of V logits: bf16 rows with V % 8 == 0 stay in registers up to V = 65536,
+// everything else is staged in LDS (row bytes <= 64 KB - 256)
+bool ce_row_fits(int dtype, int V);
 int k_cross_entropy(hipStream_t st, int dtype, void* logits, const int32_t* targets, const int32_t* n_valid, float* rowloss, int T, int V);
 void k_loss_reduce(hipStream_t st, const float* rowloss, const int32_t* n_valid, float* loss, int T);
 void k_transpose(hipStream_t st, int dtype, const void* src, int ld_src, void* dst, int ld_dst, int rows, int cols);

@@ -374,7 +374,7 @@ __global__ void cross_entropy_kernel(T* logits, const int32_t* __restrict__ targ
     row[i] = from_f32<T>(p * inv_n);
   }
 }
-// bf16 rows of up to 512 * 8 * NV logits, V % 8 == 0: the row lives in registers (NV 16-byte pieces per thread, loaded and
+// bf16 rows of up to 512 * 8 * NV logits (NV <= 16: 65536), V % 8 == 0: the row lives in registers (NV 16-byte pieces per thread, loaded and
 // stored with consecutive lanes on consecutive pieces), so there is one HBM read, one HBM write and no LDS staging.
 template <int NV>
 __global__ __launch_bounds__(512) void cross_entropy_reg_kernel(bf16_t* logits, const int32_t* __restrict__ targets,
@@ -432,14 +432,19 @@ __global__ __launch_bounds__(512) void cross_entropy_reg_kernel(bf16_t* logits, 
     row[i] = make_uint4(o[0], o[1], o[2], o[3]);
   }
 }
+bool ce_row_fits(int dtype, int V) {
+  if (dtype == 1 && V % 8 == 0 && V <= 512 * 8 * 16) return true;
+  return (size_t)V * (dtype == 0 ? 4 : 2) <= 64 * 1024 - 256;
+}
 int k_cross_entropy(hipStream_t st, int dtype, void* logits, const int32_t* targets, const int32_t* n_valid, float* rowloss, int T_, int V) {
-  if (dtype == 1 && V % 8 == 0 && V <= 512 * 8 * 8 && ((uintptr_t)logits & 15) == 0) {
+  if (dtype == 1 && V % 8 == 0 && V <= 512 * 8 * 16 && ((uintptr_t)logits & 15) == 0) {
     const int nv = (V / 8 + 511) / 512;
     bf16_t* lg = (bf16_t*)logits;
     if (nv <= 1) cross_entropy_reg_kernel<1><<<T_, 512, 0, st>>>(lg, targets, n_valid, rowloss, V);
     else if (nv <= 2) cross_entropy_reg_kernel<2><<<T_, 512, 0, st>>>(lg, targets, n_valid, rowloss, V);
     else if (nv <= 4) cross_entropy_reg_kernel<4><<<T_, 512, 0, st>>>(lg, targets, n_valid, rowloss, V);
-    else cross_entropy_reg_kernel<8><<<T_, 512, 0, st>>>(lg, targets, n_valid, rowloss, V);
+    else if (nv <= 8) cross_entropy_reg_kernel<8><<<T_, 512, 0, st>>>(lg, targets, n_valid, rowloss, V);
+    else cross_entropy_reg_kernel<16><<<T_, 512, 0, st>>>(lg, targets, n_valid, rowloss, V);
     return 0;
   }
   size_t smem = (size_t)V * (dtype == 0 ? 4 : 2);

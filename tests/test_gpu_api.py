@@ -125,3 +125,55 @@ def test_activation_recomputation_gives_the_same_bits_with_less_workspace(mname,
     saved = r0["activations"] - r1["activations"]
     per_layer_rest = (r0["activations"] - T * (2 * d + cfg0["vocab"]) * es) / L - T * d * es          # all but x, roughly
     assert saved > 0.9 * (L - 1) * per_layer_rest
+
+
+def test_parameters_filled_by_device_copy_give_the_same_step():
+    """The parameter buffer may be filled without pp_set_tensor (device-to-device copy, checkpoint load): the transposed
+    weight copies are formed from it when the mask is set, so loss, gradients and updated weights are bit-identical to a
+    model that was filled tensor by tensor."""
+    cfg = gen.make_config("tiny", **SMALL)
+    weights = gen.make_weights(cfg, seed=37)
+    mask = gen.paper_mlp_mask(cfg, 0, 4)
+    tok, tgt = gen.make_tokens(cfg, seed=37)
+    a = make_gpu_model(cfg, weights, mask)
+    b2 = pp.LocalStepModel(cfg, mask)
+    pp.pp_free(b2.h)                               # start again over a workspace full of junk: whatever it held must not matter
+    b2.ws.fill_(0x7f)
+    torch.cuda.synchronize()
+    b2.h = pp.pp_init_model(b2.ccfg, b2.params.data_ptr(), b2.bytes_params, b2.ws.data_ptr(), b2.bytes_ws, b2.stream.cuda_stream)
+    b2.params.copy_(a.params)                      # device copy of the canonical buffer; no pp_set_tensor at all
+    torch.cuda.synchronize()
+    b2.set_mask()
+    out = []
+    for mdl in (a, b2):
+        loss = float(mdl.step(*mdl.upload_tokens(tok, tgt), HP).item())
+        out.append((loss, mdl.get_state("g").copy(), mdl.get_state("p").copy(),
+                    mdl.get_weight("layers.1.wd", (cfg["d_ff"], cfg["d_model"])).copy(),
+                    mdl.get_weight("shadow.layers.1.wd", (cfg["d_model"], cfg["d_ff"])).copy()))
+    assert out[0][0] == out[1][0]
+    for x, y in zip(out[0][1:], out[1][1:]):
+        assert np.array_equal(x, y)
+    assert np.array_equal(out[1][3].T, out[1][4])
+    a.close()
+    b2.close()
+
+
+def test_vocab_above_32768_uses_the_register_cross_entropy():
+    """bf16 rows of up to 65536 logits stay in registers (no LDS stage): a one-layer model with vocab 40000 against the oracle."""
+    from oracle import pp_oracle as O
+    from harness import cosine
+    cfg = gen.make_config("tiny", n_layers=1, d_model=128, n_heads=2, d_ff=256, vocab=40000, batch=1, seq=24, dtype="bf16")
+    weights = gen.make_weights(cfg, seed=43)
+    mask = dict(gen.ffn_slice_mask(cfg, 0, 4), train_lm_head=1)
+    tok, tgt = gen.make_tokens(cfg, seed=43)
+    m = make_gpu_model(cfg, weights, mask)
+    loss = float(m.step(*m.upload_tokens(tok, tgt), None).item())
+    params = O.to_f64(weights)
+    loss_ref, cache = O.forward(cfg, params, tok, tgt)
+    g_ref, _ = O.backward_restricted(cfg, params, cache, mask)
+    assert abs(loss - loss_ref) <= 1e-2 * abs(loss_ref)
+    assert cosine(m.get_state("g"), g_ref) >= 0.999
+    m.close()
+    lib = pp.load_library()
+    too_big = b.make_config(dict(cfg, vocab=65544))
+    assert lib.pp_query_bytes(ctypes.byref(too_big), None, 0) == 0 and b"vocab" in lib.pp_last_error()

@@ -163,3 +163,54 @@ def test_two_rounds_of_algorithm_1_track_the_oracle():
         assert np.array_equal(m.get_state("p"), tg.cpu().numpy())
     assert frozen_bytes_equal(cfg, m, weights, mask) == []
     m.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_more_than_65535_packed_rows_through_adamw_and_outer_step(dtype):
+    """A narrow, deep-FFN model with every parameter trainable has 76 k packed rows of d_model = 64 elements -- more than
+    one grid dimension of 65535 would cover.  AdamW on all of them, then the outer step, against the oracle."""
+    cfg = gen.make_config("tiny", n_layers=6, d_model=64, n_heads=4, d_ff=4096, vocab=256, batch=2, seq=16, dtype=dtype)
+    weights = gen.make_weights(cfg, seed=61)
+    mask = gen.all_mask(cfg)
+    m = make_gpu_model(cfg, weights, dict(all=1))
+    segs = O.mask_segments(cfg, mask)
+    n_rows = sum(hi - lo for _, lo, hi in segs)
+    assert n_rows > 65535, n_rows
+    tok, tgt = gen.make_tokens(cfg, seed=61)
+    tr = O.LocalTrainer(cfg, weights, mask)
+    p0 = tr.master.copy()
+    loss = float(m.step(*m.upload_tokens(tok, tgt), HP).item())
+    loss_ref, g_ref = tr.step(tok, tgt, HP)
+    tol = 1e-5 if dtype == "f32" else 1e-2
+    assert abs(loss - loss_ref) <= tol * abs(loss_ref)
+    p = m.get_state("p").astype(np.float64)
+    rows = p.size // cfg["d_model"]
+    assert rows == n_rows
+    if dtype == "f32":
+        big = np.abs(g_ref) > 1e-3 * np.max(np.abs(g_ref))
+        assert np.max(np.abs((p - p0) - (tr.master - p0))[big]) <= 2e-2 * HP["lr"]
+    # every packed row moved (decay and update reach the last rows too) and the first / last rows match the oracle
+    moved = np.any((p != p0.astype(np.float32)).reshape(rows, -1), axis=1)
+    gains = (O.decay_mask_for(cfg, mask).reshape(rows, -1)[:, 0] == 0)
+    assert np.all(moved | gains)
+    from harness import cosine
+    assert cosine(p - p0, tr.master - p0) >= (0.9999 if dtype == "f32" else 0.97)
+    names = gen.tensor_shapes(cfg)
+    now = O.pack({k: m.get_weight(k, s).astype(np.float64) for k, s in names.items()}, segs).astype(np.float32)
+    expect = m.get_state("p")
+    expect = gen.round_to_bf16(expect) if dtype == "bf16" else expect
+    assert np.array_equal(now, expect)
+    # outer step over all 76 k rows
+    n = p.size
+    theta_g0 = p0.astype(np.float32)
+    tg = torch.from_numpy(theta_g0.copy()).cuda()
+    mom = torch.zeros(n, dtype=torch.float32, device="cuda")
+    delta = torch.empty(n, dtype=torch.float32, device="cuda")
+    pp.pp_outer_delta(m.h, tg.data_ptr(), mom.data_ptr(), None, pp.PPOuter(0.7, 0.9, 1, 2.0), delta.data_ptr())
+    torch.cuda.synchronize()
+    ref_new, buf, ref_delta = O.outer_step(theta_g0.astype(np.float64), now.astype(np.float64), None, np.zeros(n), 0.7, 0.9, 2.0)
+    np.testing.assert_allclose(delta.cpu().numpy(), ref_delta, rtol=2e-5, atol=1e-9)
+    np.testing.assert_allclose(tg.cpu().numpy(), ref_new, rtol=2e-6, atol=1e-8)
+    np.testing.assert_allclose(mom.cpu().numpy(), buf, rtol=2e-5, atol=1e-9)
+    assert np.array_equal(m.get_state("p"), tg.cpu().numpy())
+    m.close()

@@ -15,7 +15,37 @@ def _bf16_to_f32(raw_u16):
     return (raw_u16.astype(np.uint32) << 16).view(np.float32)
 
 
-def run_case(cfg, mask, seed, batch=None, seq=None, force_plain=False, loss_tol=1e-2, cos_tol=0.999):
+def check_update(cfg, m, omask, weights, g_ref, hp, step=1):
+    """After the AdamW step of the HIP path: packed fp32 master / m / v against the oracle's AdamW fed the ORACLE's
+    gradient (Alg. 1, InnerOpt line), on the elements whose gradient is well determined (|g| >= a quarter of its tensor's
+    rms: a bf16-level error of a few per cent of the rms cannot flip their sign, and at step 1 the update is lr * sign(g));
+    then, bit for bit: stored weights == bf16 rounding (nearest even) of the master, and a transposed copy == its matrix."""
+    segs = O.mask_segments(cfg, omask)
+    p0 = O.pack(O.to_f64(weights), segs)
+    decay = O.decay_mask_for(cfg, omask)
+    p_ref, m_ref, v_ref = O.adamw_update(p0, np.zeros_like(p0), np.zeros_like(p0), g_ref, step, hp["lr"], hp["beta1"], hp["beta2"],
+                                         hp["eps"], hp["weight_decay"], decay)
+    p_gpu, m_gpu, v_gpu = (m.get_state(k).astype(np.float64) for k in ("p", "m", "v"))
+    for name, off, n in segment_slices(cfg, omask):
+        sl = slice(off, off + n)
+        nz = g_ref[sl] != 0          # embedding rows of tokens that do not occur have no gradient at all
+        if not nz.any():
+            continue
+        rms = np.sqrt(np.mean(g_ref[sl][nz] ** 2))
+        sure = np.abs(g_ref[sl]) >= 0.25 * rms
+        assert sure.any(), name
+        assert np.max(np.abs((p_gpu[sl] - p0[sl]) - (p_ref[sl] - p0[sl]))[sure]) <= 2e-2 * hp["lr"], name
+        assert cosine(m_gpu[sl], m_ref[sl]) >= 0.999, name
+        assert cosine(v_gpu[sl], v_ref[sl]) >= 0.995, name
+    shapes = gen.tensor_shapes(cfg)
+    now = O.pack({k: m.get_weight(k, s).astype(np.float64) for k, s in shapes.items()}, segs).astype(np.float32)
+    assert np.array_equal(now.view(np.uint32), gen.round_to_bf16(m.get_state("p")).view(np.uint32))
+    l = cfg["n_layers"] - 1
+    wd = m.get_weight(f"layers.{l}.wd", (cfg["d_ff"], cfg["d_model"]))
+    assert np.array_equal(wd.T, m.get_weight(f"shadow.layers.{l}.wd", (cfg["d_model"], cfg["d_ff"])))
+
+
+def run_case(cfg, mask, seed, batch=None, seq=None, force_plain=False, loss_tol=1e-2, cos_tol=0.999, expect_mfma=None):
     weights = gen.make_weights(cfg, seed=seed)
     tok, tgt = gen.make_tokens(cfg, seed=seed, batch=batch, seq=seq)
     omask = expand_mask(cfg, mask)
@@ -37,7 +67,13 @@ def run_case(cfg, mask, seed, batch=None, seq=None, force_plain=False, loss_tol=
     assert cnt["flops_fwd"] == O.flops_forward(cfg, B, S)
     assert cnt["flops_bwd"] == info["flops_bwd"]
     assert frozen_bytes_equal(cfg, m, weights, mask) == []
-    print(f"loss gpu {loss_gpu:.5f} oracle {loss_ref:.5f}; worst gradient cosine {worst:.6f}", flush=True)
+    check_update(cfg, m, omask, weights, g_ref, HP)
+    lc = m.launch_counts()
+    if force_plain:
+        assert lc["matrix_core_calls"] == 0 and lc["plain_calls"] > 0, lc
+    if expect_mfma:
+        assert lc["plain_calls"] == 0 and lc["matrix_core_calls"] > 0, lc
+    print(f"loss gpu {loss_gpu:.5f} oracle {loss_ref:.5f}; worst gradient cosine {worst:.6f}; launches {lc}", flush=True)
     m.close()
 
 
@@ -60,7 +96,68 @@ def test_125m_shape_step_matches_oracle_on_two_sequences():
     fp64 oracle finishes in well under a minute; 1/8 FFN slice."""
     cfg = gen.make_config("125m")
     print("case 125m B=2", flush=True)
-    run_case(cfg, gen.ffn_slice_mask(cfg, 0, 8), seed=5, batch=2)
+    run_case(cfg, gen.ffn_slice_mask(cfg, 0, 8), seed=5, batch=2, expect_mfma=True)
+
+
+def test_125m_shape_loss_curve_and_masters_track_the_oracle_for_four_steps():
+    """Config-2 shape, 2 x 1024 tokens per step, H = 4 steps of Alg. 1's inner loop with the update applied: the loss of
+    every step within 1e-2 of the oracle's trainer that keeps a full-precision master and a bf16 compute copy, the masters'
+    total displacement aligned with the oracle's, every frozen byte unchanged, matrix-core kernels throughout."""
+    cfg = gen.make_config("125m")
+    mask = gen.ffn_slice_mask(cfg, 5, 8)
+    weights = gen.make_weights(cfg, seed=6)
+    m = make_gpu_model(dict(cfg, batch=2), weights, mask)
+    tr = O.LocalTrainer(cfg, weights, mask, storage="bf16")
+    p0 = tr.master.copy()
+    print("case 125m H=4 trajectory", flush=True)
+    for h in range(4):
+        tok, tgt = gen.make_tokens(cfg, seed=6, step=h, batch=2)
+        lg = float(m.step(*m.upload_tokens(tok, tgt), HP).item())
+        lo, _ = tr.step(tok, tgt, HP, restricted=True)
+        print(f"step {h}: loss gpu {lg:.5f} oracle {lo:.5f}", flush=True)
+        assert abs(lg - lo) <= 1e-2 * abs(lo), (h, lg, lo)
+        lc = m.launch_counts()
+        assert lc["plain_calls"] == 0 and lc["matrix_core_calls"] > 0, lc
+    p = m.get_state("p").astype(np.float64)
+    c = cosine(p - p0, tr.master - p0)
+    print(f"displacement cosine after 4 steps {c:.5f}", flush=True)
+    assert c >= 0.97
+    assert np.max(np.abs(p - tr.master)) <= 2 * 4 * HP["lr"]
+    assert frozen_bytes_equal(cfg, m, weights, mask) == []
+    m.close()
+
+
+@pytest.mark.parametrize("mname", ["ffn", "paper_mlp"])
+def test_small_bf16_ten_step_trajectory_tracks_the_oracle(mname):
+    """Ten consecutive local steps on the multi-tile small model (update applied every step, fresh batch every step)
+    against the oracle's trainer with full-precision master + bf16 compute copy: loss within 1e-2 at every step; masters:
+    displacement cosine >= 0.97 and every element within 2 * H * lr (AdamW moves an element by about lr per step, so two
+    runs can drift apart by at most about twice that per step where a gradient's sign is noise); m and v aligned; stored
+    weights bit-equal to the bf16 rounding of the master."""
+    cfg = gen.make_config("tiny", **SMALL)
+    mask = {"ffn": gen.ffn_slice_mask(cfg, 1, 4), "paper_mlp": gen.paper_mlp_mask(cfg, 1, 4)}[mname]
+    weights = gen.make_weights(cfg, seed=13)
+    m = make_gpu_model(cfg, weights, mask)
+    tr = O.LocalTrainer(cfg, weights, mask, storage="bf16")
+    p0 = tr.master.copy()
+    H = 10
+    print(f"case small-bf16 trajectory/{mname}", flush=True)
+    for h in range(H):
+        tok, tgt = gen.make_tokens(cfg, seed=13, step=h)
+        lg = float(m.step(*m.upload_tokens(tok, tgt), HP).item())
+        lo, _ = tr.step(tok, tgt, HP)
+        assert abs(lg - lo) <= 1e-2 * abs(lo), (h, lg, lo)
+    p, mm, vv = (m.get_state(k).astype(np.float64) for k in ("p", "m", "v"))
+    cp, cm, cv = cosine(p - p0, tr.master - p0), cosine(mm, tr.m), cosine(vv, tr.v)
+    print(f"after {H} steps: displacement cosine {cp:.5f}, m cosine {cm:.5f}, v cosine {cv:.5f}, "
+          f"max |p - p_ref| / lr {np.max(np.abs(p - tr.master)) / HP['lr']:.2f}", flush=True)
+    assert cp >= 0.97 and cm >= 0.99 and cv >= 0.99
+    assert np.max(np.abs(p - tr.master)) <= 2 * H * HP["lr"]
+    segs = O.mask_segments(cfg, mask)
+    now = O.pack({k: m.get_weight(k, s).astype(np.float64) for k, s in gen.tensor_shapes(cfg).items()}, segs).astype(np.float32)
+    assert np.array_equal(now.view(np.uint32), gen.round_to_bf16(m.get_state("p")).view(np.uint32))
+    assert frozen_bytes_equal(cfg, m, weights, mask) == []
+    m.close()
 
 
 def test_125m_fifty_steps_leave_frozen_parameters_bit_identical():
@@ -113,6 +210,9 @@ def test_1p3b_shape_step_matches_oracle_on_one_sequence():
     assert worst >= 0.999
     assert cnt["flops_fwd"] + cnt["flops_bwd"] == O.flops_forward(cfg, 1, 2048) + info["flops_bwd"]
     assert frozen_bytes_equal(cfg, m, weights, mask) == []
+    lc = m.launch_counts()
+    assert lc["plain_calls"] == 0 and lc["matrix_core_calls"] > 0, lc
+    check_update(cfg, m, mask, weights, g_ref, HP)
     m.close()
 
     # The full batch 8 x 2048 exactly as bench.py launches it.  Causality makes the hidden states of the first positions
@@ -141,6 +241,8 @@ def test_1p3b_shape_step_matches_oracle_on_one_sequence():
     # Then a full step with all targets and the update; forward checked on the same prefix.
     loss8 = float(m8.step(*m8.upload_tokens(tok8, tgt8), HP).item())
     cnt8 = m8.counters()
+    lc8 = m8.launch_counts()
+    assert lc8["plain_calls"] == 0 and lc8["matrix_core_calls"] > 0, lc8
     B8, S8 = tok8.shape
     assert np.isfinite(loss8)
     assert cnt8["flops_fwd"] + cnt8["flops_bwd"] == O.flops_forward(cfg, B8, S8) + O.flops_backward_ffn_slice(cfg, B8, S8, 1.0 / 32)

@@ -23,6 +23,21 @@ extern "C" {
 int pp_op_gemm_nt(void* hip_stream, int dtype, const void* A_dev, int lda, const void* B_dev, int ldb, void* C_dev, int ldc,
                   int M, int N, int K, const void* R_dev, int out_f32, int splits, float* scratch_dev, int path);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): the split-K form of pp_op_gemm_nt with fp32 output, C[M x N] (ldc) = A[M x K] * B[N x K]^T, whose
+ * partial products [splits][M][N] live in a 16 MiB device array built into the library instead of a caller's scratch
+ * buffer.  Same kernels, same summation order and therefore the same bits as pp_op_gemm_nt(..., out_f32 = 1, splits,
+ * scratch, path).  Requirements: splits >= 2, K % splits == 0, M*N*splits <= PP_STATIC_SCRATCH_FLOATS, else PP_EINVAL
+ * with a message that names the limit.  Calls no hipMalloc / hipFree and nothing that allocates; only enqueues on
+ * hip_stream.  The first call on a GPU also looks up that GPU's address of the array (the HIP runtime materialises a
+ * module's device variables at that moment: make one call per GPU before entering a region that must not allocate).
+ * Every call on one GPU uses that GPU's one array (it keeps the previous call's partials; each call overwrites all it
+ * reads): calls that overlap on one GPU -- different streams or threads -- race; calls on one stream are ordered and
+ * safe.  Each GPU the library runs on holds its own 16 MiB until process exit. */
+#define PP_STATIC_SCRATCH_FLOATS (4u << 20)
+int pp_op_gemm_nt_splitk_static(void* hip_stream, int dtype, const void* A_dev, int lda, const void* B_dev, int ldb, float* C_dev,
+                                int ldc, int M, int N, int K, int splits, int path);
+
 /* Causal softmax attention (Appendix "MHA with frozen heads", forward of every head; mask from the autoregressive
  * factorisation of Section 2.1).  qkv_dev: [B*S x 3*h*dh], columns q | k | v, head j at columns j*dh of each part
  * (q and k already rotated).  o_dev: [B*S x h*dh].  lse_dev: float [B*h*S], log-sum-exp of the scaled scores.

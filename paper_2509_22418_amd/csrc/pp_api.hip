@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -880,6 +881,50 @@ extern "C" int pp_op_gemm_nt(void* hip_stream, int dtype, const void* A, int lda
   if (splits > 1) k_splitk_reduce(st, scratch, (float*)C, ldc, M, N, splits);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(PP_EHIP, std::string("pp_op_gemm_nt: ") + hipGetErrorString(e));
+  return PP_OK;
+}
+
+// ---- split-K GEMM for callers that cannot allocate: the partial products live in a file-scope device array
+constexpr size_t kStaticScratchFloats = PP_STATIC_SCRATCH_FLOATS;          // 16 MiB per GPU, held until the process ends
+static __device__ __align__(256) float scratch[kStaticScratchFloats];
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static float* g_scratch_ptr[kMaxDevices];          // device address of `scratch` on each GPU (each GPU has its own copy), nullptr = not asked yet
+
+// Device address of the current GPU's copy of `scratch` (looked up once per device, with that device current).
+static int static_scratch(float** out) {
+  int dev = -1;
+  HIPCHECK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(PP_EINVAL, "static scratch: device index out of range");
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    float* p = nullptr;
+    HIPCHECK(hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(PP_EHIP, "static scratch: hipGetSymbolAddress returned a null address");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return PP_OK;
+}
+
+extern "C" int pp_op_gemm_nt_splitk_static(void* hip_stream, int dtype, const void* A, int lda, const void* B, int ldb, float* C, int ldc,
+                                           int M, int N, int K, int splits, int path) {
+  if (!A || !B || !C) return fail(PP_EINVAL, "pp_op_gemm_nt_splitk_static: NULL pointer");
+  if (dtype != PP_F32 && dtype != PP_BF16) return fail(PP_EINVAL, "pp_op_gemm_nt_splitk_static: bad dtype");
+  if (M < 1 || N < 1 || K < 1 || lda < K || ldb < K || ldc < N) return fail(PP_EINVAL, "pp_op_gemm_nt_splitk_static: bad shape or leading dimension");
+  if (splits < 2 || K % splits) return fail(PP_EINVAL, "pp_op_gemm_nt_splitk_static: splits must be >= 2 and divide K");
+  if ((size_t)M * (size_t)N > kStaticScratchFloats / (size_t)splits)
+    return fail(PP_EINVAL, "pp_op_gemm_nt_splitk_static: M*N*splits exceeds the built-in scratch of " + std::to_string(kStaticScratchFloats) +
+                               " floats (use pp_op_gemm_nt with a scratch buffer of your own)");
+  float* part = nullptr;
+  if (int rc = static_scratch(&part)) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  // every element [z][row < M][col < N] of the partials is written by the GEMM before the reduction reads it: nothing to clear
+  if (!(path == 0 && dtype == PP_BF16 && k_gemm_nt_mfma(st, A, lda, B, ldb, C, ldc, M, N, K, EPI_STORE, nullptr, 1, splits, part) == 0))
+    k_gemm_nt_plain_splitk(st, dtype, A, lda, B, ldb, part, M, N, K, splits);
+  k_splitk_reduce(st, part, C, ldc, M, N, splits);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(PP_EHIP, std::string("pp_op_gemm_nt_splitk_static: ") + hipGetErrorString(e));
   return PP_OK;
 }
 

@@ -99,7 +99,7 @@ class PowerSampler:
                     source="hwmon power1_input, sampled every 20 ms over the timed steps (the driver's reading is itself smoothed)")
 
 
-def run_leg(torch, pp, gen, cfg, weights, mask, batches, steps, warmup, time_gemm, outer=False, seed=0):
+def run_leg(torch, pp, gen, cfg, weights, mask, batches, steps, warmup, time_gemm, outer=False, seed=0, options=()):
     torch.cuda.synchronize()
     torch.cuda.empty_cache()
     torch.cuda.reset_peak_memory_stats()
@@ -107,6 +107,8 @@ def run_leg(torch, pp, gen, cfg, weights, mask, batches, steps, warmup, time_gem
     m = pp.LocalStepModel({k: v for k, v in cfg.items() if k != "detach_jacobian"}, mask)
     m.load_weights(weights)
     m.set_mask()
+    for key, value in options:
+        m.set_option(key, value)
     if detach:
         m.set_jacobian_slices(1)
     dev = [m.upload_tokens(t, g) for t, g in batches]
@@ -212,6 +214,8 @@ def main():
     ap.add_argument("--legs", default="all", help="'main' = only the headline mask; 'all' = also rho=1/8 and all-trainable")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=1234)
+    ap.add_argument("--set", action="append", default=[], metavar="KEY=INT",
+                    help="library option for every leg's model (pp_set_option), e.g. --set dw_tn=0 for a same-box A/B")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run three plain 1 GiB streaming copies (torch neg kernel, out = -in): under rocprofv3 --pmc FETCH_SIZE / "
                          "WRITE_SIZE their readings give the counter scale for the HBM-traffic figures")
@@ -260,7 +264,7 @@ def main():
     for name, mask, rho, leg_cfg in legs:
         t1 = time.perf_counter()
         r = run_leg(torch, pp, gen, leg_cfg, weights, mask, batches, args.steps, args.warmup, time_gemm=True,
-                    outer=(name == legs[0][0]), seed=args.seed)
+                    outer=(name == legs[0][0]), seed=args.seed, options=[(kv.split("=")[0], int(kv.split("=")[1])) for kv in args.set])
         fwd, bwd = closed_form_flops(cfg, B, S, rho, detach=bool(leg_cfg.get("detach_jacobian")))
         ms = r["seconds"] / args.steps * 1e3
         executed = r["counters"]["flops_fwd"] + r["counters"]["flops_bwd"]

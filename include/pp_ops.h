@@ -23,6 +23,17 @@ extern "C" {
 int pp_op_gemm_nt(void* hip_stream, int dtype, const void* A_dev, int lda, const void* B_dev, int ldb, void* C_dev, int ldc,
                   int M, int N, int K, const void* R_dev, int out_f32, int splits, float* scratch_dev, int path);
 
+/* The weight-gradient contraction in the layout the step has it in (Appendix "Partial Backward": dW_n = dH_n X^T,
+ * dV_n = G A_n^T, with tokens as the contraction index): C[M x N] (float, ldc) = A^T B, A: [K x .] and B: [K x N] row-major
+ * bf16 with leading dimensions lda, ldb -- both token-major, no transposed copies.  Column m of the product is column
+ * (m / m_blk) * a_blk_stride + m % m_blk of A (m_blk = M, a_blk_stride = 0 for one contiguous column range).
+ * splits > 1 (scratch_dev of M*N*splits floats): K is cut into `splits` equal ranges whose partial products are summed in
+ * fixed order.  MFMA kernel only (bf16): needs M, N, lda, ldb, m_blk, a_blk_stride multiples of 8, K a multiple of
+ * 64*splits, and m_blk a multiple of 128 when M > m_blk; other shapes return PP_EINVAL (pp_local_step then goes through
+ * transposed copies and pp_op_gemm_nt's kernels instead). */
+int pp_op_gemm_tn(void* hip_stream, const void* A_dev, int lda, int m_blk, int64_t a_blk_stride, const void* B_dev, int ldb, float* C_dev,
+                  int ldc, int M, int N, int K, int splits, float* scratch_dev);
+
 /* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that
  * forbid hipMalloc): the split-K form of pp_op_gemm_nt with fp32 output, C[M x N] (ldc) = A[M x K] * B[N x K]^T, whose
  * partial products [splits][M][N] live in a 16 MiB device array built into the library instead of a caller's scratch

@@ -16,7 +16,7 @@ PP_STATIC_SCRATCH_FLOATS = 4 << 20          # include/pp_ops.h
 PP_BYTES_PARAMS, PP_BYTES_STATE, PP_BYTES_WORKSPACE, PP_BYTES_SHADOW, PP_BYTES_ACTIVATIONS = range(5)
 EXPORTS = ["pp_query_bytes", "pp_init_model", "pp_set_tensor", "pp_get_tensor", "pp_set_trainable_mask", "pp_local_step",
            "pp_set_jacobian_slices", "pp_outer_delta", "pp_outer_delta_group", "pp_synth_delta_sum", "pp_get_counters", "pp_get_launch_counts", "pp_get_gemm_timing", "pp_set_option", "pp_last_error", "pp_free",
-           "pp_op_gemm_nt", "pp_op_gemm_nt_splitk_static", "pp_op_attention_fwd", "pp_op_attention_bwd"]
+           "pp_op_gemm_nt", "pp_op_gemm_tn", "pp_op_gemm_nt_splitk_static", "pp_op_attention_fwd", "pp_op_attention_bwd"]
 
 
 class PPError(RuntimeError):
@@ -94,6 +94,8 @@ def load_library():
     lib.pp_free.argtypes = [vp]
     lib.pp_op_gemm_nt.restype = C.c_int
     lib.pp_op_gemm_nt.argtypes = [vp, C.c_int, vp, C.c_int, vp, C.c_int, vp, C.c_int, C.c_int, C.c_int, C.c_int, vp, C.c_int, C.c_int, vp, C.c_int]
+    lib.pp_op_gemm_tn.restype = C.c_int
+    lib.pp_op_gemm_tn.argtypes = [vp, vp, C.c_int, C.c_int, i64, vp, C.c_int, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, vp]
     lib.pp_op_gemm_nt_splitk_static.restype = C.c_int
     lib.pp_op_gemm_nt_splitk_static.argtypes = [vp, C.c_int, vp, C.c_int, vp, C.c_int, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]
     lib.pp_op_attention_fwd.restype = C.c_int
@@ -199,6 +201,10 @@ def pp_op_gemm_nt(stream: int, dtype: int, A_ptr, lda, B_ptr, ldb, C_ptr, ldc, M
                   scratch_ptr=None, path=0):
     _check(load_library().pp_op_gemm_nt(stream, dtype, A_ptr, lda, B_ptr, ldb, C_ptr, ldc, M, N, K, R_ptr, out_f32, splits,
                                         scratch_ptr, path), "pp_op_gemm_nt")
+
+
+def pp_op_gemm_tn(stream: int, A_ptr, lda, m_blk, a_blk_stride, B_ptr, ldb, C_ptr, ldc, M, N, K, splits=1, scratch_ptr=None):
+    _check(load_library().pp_op_gemm_tn(stream, A_ptr, lda, m_blk, a_blk_stride, B_ptr, ldb, C_ptr, ldc, M, N, K, splits, scratch_ptr), "pp_op_gemm_tn")
 
 
 def pp_op_gemm_nt_splitk_static(stream: int, dtype: int, A_ptr, lda, B_ptr, ldb, C_ptr, ldc, M, N, K, splits, path=0):

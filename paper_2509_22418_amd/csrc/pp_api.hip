@@ -164,6 +164,7 @@ struct pp_model {
   float *sp = nullptr, *sm = nullptr, *sv = nullptr, *sg = nullptr;
   long step = 0;
   int force_plain = 0;
+  int dw_tn = 1;          // weight-gradient GEMMs read token-major operands directly (0: via transposed copies, for A/B timing)
   int jac_mode = 0, jac_lo = 0, jac_hi = 0;          // ablation: FFN input Jacobian over the trainable slice (+ units jac_lo..jac_hi-1) only
   double flops_fwd = 0, flops_bwd = 0, flops_recompute = 0, adamw_bytes = 0;
   int64_t n_mfma = 0, n_plain = 0;          // contractions (GEMM / attention calls) of the last step by kernel family
@@ -339,6 +340,7 @@ extern "C" int pp_set_option(pp_model* m, const char* key, int64_t value) {
   if (key && !strcmp(key, "gemm_persistent")) { gemm_set_persistent(value != 0); return PP_OK; }
   if (!m || !key) return fail(PP_EINVAL, "pp_set_option: NULL");
   if (!strcmp(key, "force_plain")) { m->force_plain = value != 0; return PP_OK; }
+  if (!strcmp(key, "dw_tn")) { m->dw_tn = value != 0; return PP_OK; }
   if (!strcmp(key, "gemm_variant")) { gemm_set_variant((int)value); return PP_OK; }
   if (!strcmp(key, "time_gemm")) {
     if (hipStreamSynchronize(m->st) != hipSuccess) return fail(PP_EHIP, "pp_set_option: stream sync failed");
@@ -554,6 +556,39 @@ static void gemm_dw(pp_model* m, const void* At, const void* Bt, float* G, int M
   k_splitk_reduce(m->st, partial, G, N, M, N, splits);
 }
 
+// Weight gradient from token-major operands: G[M x N] (fp32, ld N) = A^T B, A [K x M'] (lda) and B [K x N] (ldb) as the
+// forward / backward passes left them, K = tokens; column m of the product is column (m / m_blk) * a_blk_stride + m % m_blk
+// of A.  The MFMA kernel gathers its operands with LDS transpose reads; shapes it does not take (and fp32 storage) go
+// through transposed copies and gemm_dw.
+static void gemm_dw_tn(pp_model* m, const void* A, int lda, int m_blk, long a_blk_stride, const void* B, int ldb, float* G, int M, int N, int K) {
+  const size_t es = esize(m->cfg);
+  // (measured at K = 16384: up to 256 tiles of 128 x 128 -- the row-block slices, which need split-K anyway, and d x d --
+  // the transpose-read kernel beats transposing both operands and running the 256 x 256-tile NT kernel; above that the
+  // NT kernel's higher rate outweighs the two extra passes)
+  const long tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
+  if (m->cfg.dtype == PP_BF16 && !m->force_plain && m->dw_tn && tiles <= 256) {
+    const size_t out_bytes = (size_t)M * N * 4;
+    int splits = 1;
+    while (splits < 32 && tiles * splits < 512 && K % (splits * 2 * 64) == 0 && K / (splits * 2) >= 256 &&
+           out_bytes * (size_t)(splits * 2) <= m->ws.partial_bytes) splits *= 2;
+    float* partial = (float*)(m->wsp + m->ws.partial);
+    GemmTimer timer(m, 2.0 * M * N * K);
+    if (k_gemm_tn_mfma(m->st, A, lda, m_blk, a_blk_stride, B, ldb, G, N, M, N, K, splits, partial) == 0) {
+      if (splits > 1) k_splitk_reduce(m->st, partial, G, N, M, N, splits);
+      if (m->flop_acc) *m->flop_acc += 2.0 * M * N * K;
+      m->n_mfma++;
+      return;
+    }
+    timer.cancel();
+  }
+  char* tA = m->wsp + m->ws.tA;
+  char* tB = m->wsp + m->ws.tB;
+  for (int b0 = 0; b0 < M; b0 += m_blk)
+    k_transpose(m->st, m->cfg.dtype, (const char*)A + (size_t)(b0 / m_blk) * a_blk_stride * es, lda, tA + (size_t)b0 * K * es, K, K, std::min(m_blk, M - b0));
+  k_transpose(m->st, m->cfg.dtype, B, ldb, tB, K, K, N);
+  gemm_dw(m, tA, tB, G, M, N, K);
+}
+
 static void attn_fwd(pp_model* m, const void* qkv, void* o, float* lse, int B, int S) {
   const int h = m->cfg.n_heads, dh = m->cfg.d_model / h;
   if (m->flop_acc) *m->flop_acc += 4.0 * ((double)B * S * (S + 1) / 2) * m->cfg.d_model;
@@ -644,8 +679,6 @@ extern "C" int pp_local_step(pp_model* m, const int32_t* tokens_dev, const int32
   m->flop_acc = &m->flops_bwd;
   const bool any_layer = mk.norms || mk.heads || mk.wo || mk.ffn;
   auto below_layer = [&](int l) { return mk.emb || (l > 0 && any_layer); };
-  void* tA = W + w.tA;
-  void* tB = W + w.tB;
   void* dx = W + w.dx;
   void* dn = W + w.dn;
   void* dA = W + w.dA;
@@ -658,11 +691,7 @@ extern "C" int pp_local_step(pp_model* m, const int32_t* tokens_dev, const int32
   void* dz = logits;
   bool reached_bottom = false;
   if (any_layer || mk.emb || mk.lm) {
-    if (mk.lm) {
-      k_transpose(st, dt, dz, V, tA, T, T, V);
-      k_transpose(st, dt, nf, d, tB, T, T, d);
-      gemm_dw(m, tA, tB, g + find_seg(m, TK_LM_HEAD, -1)->packed_off, V, d, T);
-    }
+    if (mk.lm) gemm_dw_tn(m, dz, V, V, 0, nf, d, g + find_seg(m, TK_LM_HEAD, -1)->packed_off, V, d, T);
     if (any_layer || mk.emb) {
       gemm_nt(m, dz, V, shad(ly.sh_lm_head), V, dn, d, T, d, V);
       if (mk.norms) k_rmsnorm_dgamma(st, dt, dn, xL, rstdf, dgpart, g + find_seg(m, TK_FINAL_NORM, -1)->packed_off, T, d);
@@ -677,11 +706,8 @@ extern "C" int pp_local_step(pp_model* m, const int32_t* tokens_dev, const int32
         }
         if (mk.ffn || below_ffn_w) {
           const int c0 = below_ffn_w ? 0 : mk.fl, c1 = below_ffn_w ? F : mk.fh, nc = c1 - c0, Fk = mk.fh - mk.fl;
-          if (mk.ffn) {      // dWd_k = A_k^T G
-            k_transpose(st, dt, ofs(act(l, w.a_a), mk.fl), F, tA, T, T, Fk);
-            k_transpose(st, dt, dx, d, tB, T, T, d);
-            gemm_dw(m, tA, tB, g + find_seg(m, TK_WD, l)->packed_off, Fk, d, T);
-          }
+          if (mk.ffn)      // dWd_k = A_k^T G
+            gemm_dw_tn(m, ofs(act(l, w.a_a), mk.fl), F, Fk, 0, dx, d, g + find_seg(m, TK_WD, l)->packed_off, Fk, d, T);
           // dG, dU of hidden units r0..r1-1 into their columns of dgu
           auto ffn_dgu = [&](int r0, int r1) {
             if (!gemm_swiglu_bwd(m, dx, canon(lb + ly.o_wd + (int64_t)r0 * d), ofs(act(l, w.a_gu), r0), ofs(dgu, r0), T, r1 - r0, F, d)) {
@@ -692,12 +718,8 @@ extern "C" int pp_local_step(pp_model* m, const int32_t* tokens_dev, const int32
           const bool detach = below_ffn_w && m->jac_mode == 1;
           if (!detach) ffn_dgu(c0, c1);
           else { ffn_dgu(mk.fl, mk.fh); if (m->jac_hi > m->jac_lo) ffn_dgu(m->jac_lo, m->jac_hi); }
-          if (mk.ffn) {      // [dWg_k; dWu_k] = [dG_k; dU_k]^T Xn
-            k_transpose(st, dt, ofs(dgu, mk.fl), 2 * F, tA, T, T, Fk);
-            k_transpose(st, dt, ofs(dgu, (size_t)F + mk.fl), 2 * F, ofs(tA, (size_t)Fk * T), T, T, Fk);
-            k_transpose(st, dt, act(l, w.a_n2), d, tB, T, T, d);
-            gemm_dw(m, tA, tB, g + find_seg(m, TK_WG, l)->packed_off, 2 * Fk, d, T);
-          }
+          if (mk.ffn)      // [dWg_k; dWu_k] = [dG_k; dU_k]^T Xn: the two column blocks of dgu sit d_ff columns apart
+            gemm_dw_tn(m, ofs(dgu, mk.fl), 2 * F, Fk, F, act(l, w.a_n2), d, g + find_seg(m, TK_WG, l)->packed_off, 2 * Fk, d, T);
           if (below_ffn_w && !detach) gemm_nt(m, dgu, 2 * F, shad(sb + ly.sh_wgu), 2 * F, dn, d, T, d, 2 * F);   // dXn over ALL slices
           if (detach) {
             // Appendix "Additional Results" (detach-all-but-k, + one more slice): dXn summed over the kept units only.
@@ -720,21 +742,14 @@ extern "C" int pp_local_step(pp_model* m, const int32_t* tokens_dev, const int32
         const bool below_norm2 = mk.wo || mk.heads || mk.norms || below_layer(l);
         if (!below_norm2) break;
         k_rmsnorm_bwd(st, dt, dn, act(l, w.a_xm), (float*)act(l, w.a_rstd2), canon(lb + ly.o_ffn_norm), dx, dx, T, d);   // dx := dL/dx_mid
-        if (mk.wo) {
-          k_transpose(st, dt, dx, d, tA, T, T, d);
-          k_transpose(st, dt, act(l, w.a_o), d, tB, T, T, d);
-          gemm_dw(m, tA, tB, g + find_seg(m, TK_WO, l)->packed_off, d, d, T);
-        }
+        if (mk.wo) gemm_dw_tn(m, dx, d, d, 0, act(l, w.a_o), d, g + find_seg(m, TK_WO, l)->packed_off, d, d, T);
         const bool below_wo = mk.heads || mk.norms || below_layer(l);
         if (!below_wo) break;
         gemm_nt(m, dx, d, shad(sb + ly.sh_wo), d, dob, d, T, d, d);
         attn_bwd(m, act(l, w.a_qkv), act(l, w.a_o), (float*)act(l, w.a_lse), dob, dqkv, Dattn, B, S, cosb, sinb);
-        if (mk.heads) {
+        if (mk.heads) {      // the Q, K and V parts of the head range sit d_model columns apart in dqkv
           const int nhd = (mk.hh - mk.hl) * dh;
-          for (int blk = 0; blk < 3; ++blk)
-            k_transpose(st, dt, ofs(dqkv, (size_t)blk * d + (size_t)mk.hl * dh), 3 * d, ofs(tA, (size_t)blk * nhd * T), T, T, nhd);
-          k_transpose(st, dt, act(l, w.a_n1), d, tB, T, T, d);
-          gemm_dw(m, tA, tB, g + find_seg(m, TK_WQKV, l)->packed_off, 3 * nhd, d, T);
+          gemm_dw_tn(m, ofs(dqkv, (size_t)mk.hl * dh), 3 * d, nhd, d, act(l, w.a_n1), d, g + find_seg(m, TK_WQKV, l)->packed_off, 3 * nhd, d, T);
         }
         const bool below_wqkv = mk.norms || below_layer(l);
         if (!below_wqkv) break;
@@ -881,6 +896,21 @@ extern "C" int pp_op_gemm_nt(void* hip_stream, int dtype, const void* A, int lda
   if (splits > 1) k_splitk_reduce(st, scratch, (float*)C, ldc, M, N, splits);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(PP_EHIP, std::string("pp_op_gemm_nt: ") + hipGetErrorString(e));
+  return PP_OK;
+}
+
+extern "C" int pp_op_gemm_tn(void* hip_stream, const void* A, int lda, int m_blk, int64_t a_blk_stride, const void* B, int ldb, float* C, int ldc,
+                             int M, int N, int K, int splits, float* scratch) {
+  if (!A || !B || !C) return fail(PP_EINVAL, "pp_op_gemm_tn: NULL pointer");
+  if (M < 1 || N < 1 || K < 1 || ldb < N || ldc < N || m_blk < 1) return fail(PP_EINVAL, "pp_op_gemm_tn: bad shape or leading dimension");
+  if ((int64_t)((M - 1) / m_blk) * a_blk_stride + std::min(M, m_blk) > lda) return fail(PP_EINVAL, "pp_op_gemm_tn: column blocks of A exceed lda");
+  if (splits < 1 || (splits > 1 && !scratch)) return fail(PP_EINVAL, "pp_op_gemm_tn: split-K needs a scratch buffer");
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (k_gemm_tn_mfma(st, A, lda, m_blk, (long)a_blk_stride, B, ldb, C, ldc, M, N, K, splits, scratch) != 0)
+    return fail(PP_EINVAL, "pp_op_gemm_tn: shape or alignment not taken by the MFMA kernel (see pp_ops.h)");
+  if (splits > 1) k_splitk_reduce(st, scratch, C, ldc, M, N, splits);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(PP_EHIP, std::string("pp_op_gemm_tn: ") + hipGetErrorString(e));
   return PP_OK;
 }
 

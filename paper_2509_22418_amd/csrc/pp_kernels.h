@@ -76,6 +76,11 @@ int k_gemm_swiglu_bwd_mfma(hipStream_t st, const void* G, int ldg, const void* W
                            int M, int N, int K);
 int k_gemm_nt_mfma(hipStream_t st, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
                    int epi, const void* R, int out_f32, int splits, float* partial);
+// Weight-gradient form: C[M x N] fp32 (ldc) = A^T B with A [K x M] (lda), B [K x N] (ldb) row-major bf16 -- no transposed
+// copies.  Column m of the product is column (m / m_blk) * a_blk_stride + m % m_blk of A.  splits > 1: `partial` receives
+// [splits][M][N] and C is not written.  Returns 0 if launched, 1 if the shape is not taken.
+int k_gemm_tn_mfma(hipStream_t st, const void* A, int lda, int m_blk, long a_blk_stride, const void* B, int ldb, float* C, int ldc,
+                   int M, int N, int K, int splits, float* partial);
 void gemm_set_variant(int v);          // 0: register-staged MFMA GEMM, 1: direct-to-LDS MFMA GEMM
 void gemm_set_persistent(int v);       // 1 (default): a workgroup per compute unit walks several tiles when there are more tiles than units
 // scratch: 3 * attn_scratch_elems(B, S, h, dh) bf16 elements for the attention-transposed operand copies.

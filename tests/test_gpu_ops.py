@@ -160,3 +160,43 @@ def test_attention_fwd_bwd_matches_definition(B, S, h, dh):
         s = np.where(np.tril(np.ones((S, S), bool)), s, -np.inf)
         lse_ref = np.log(np.exp(s - s.max(-1, keepdims=True)).sum(-1)) + s.max(-1)
         assert np.max(np.abs(lse_d.cpu().numpy().reshape(B, h, S) - lse_ref)) <= 2e-3
+
+
+TN_CASES = [
+    # K (tokens), M, N, lda, m_blk, a_blk_stride, splits
+    (256, 128, 128, 128, 128, 0, 1),            # one tile
+    (512, 256, 384, 1024, 256, 0, 2),           # a column slice of a wider A (hidden-unit slice), several tiles, split K
+    (384, 256, 200, 1024, 128, 512, 1),         # two column blocks 512 apart (gate | up), ragged N
+    (1024, 72, 2048, 72, 72, 0, 4),             # ragged M inside one tile, wide N
+    (2048, 384, 136, 1536, 128, 512, 8),        # three blocks (q | k | v of a head range), ragged N tile, 8 K ranges
+]
+
+
+@pytest.mark.parametrize("K,M,N,lda,m_blk,stride,splits", TN_CASES)
+def test_gemm_tn_matches_definition(K, M, N, lda, m_blk, stride, splits):
+    """Weight-gradient form C = A^T B with both operands token-major (LDS transpose reads), against numpy fp64 on the same
+    bf16-rounded inputs; fp32 output, so the tolerance is fp32 accumulation over K."""
+    print(f"case gemm_tn K={K} M={M} N={N} lda={lda} m_blk={m_blk} stride={stride} splits={splits}", flush=True)
+    Ad, A = dev_bf16(rnd((K, lda), 5))
+    Bd, B = dev_bf16(rnd((K, N), 6))
+    cols = np.concatenate([np.arange(min(m_blk, M - b0)) + (b0 // m_blk) * stride for b0 in range(0, M, m_blk)])
+    ref = A[:, cols].T @ B
+    st = torch.cuda.current_stream().cuda_stream
+    Cd = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    scratch = torch.empty(M * N * splits, dtype=torch.float32, device="cuda") if splits > 1 else None
+    pp.pp_op_gemm_tn(st, Ad.data_ptr(), lda, m_blk, stride, Bd.data_ptr(), N, Cd.data_ptr(), N, M, N, K, splits,
+                     None if scratch is None else scratch.data_ptr())
+    torch.cuda.synchronize()
+    got = Cd.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got))
+    assert np.max(np.abs(got - ref)) <= 2e-5 * np.sqrt(K) * max(1.0, np.max(np.abs(ref)) / np.sqrt(K)) + 1e-6 * np.max(np.abs(ref))
+
+
+def test_gemm_tn_rejects_shapes_it_does_not_take():
+    st = torch.cuda.current_stream().cuda_stream
+    x = torch.zeros(1 << 16, dtype=torch.int16, device="cuda")
+    c = torch.zeros(1 << 16, dtype=torch.float32, device="cuda")
+    with pytest.raises(pp.PPError, match="not taken"):
+        pp.pp_op_gemm_tn(st, x.data_ptr(), 128, 128, 0, x.data_ptr(), 128, c.data_ptr(), 128, 128, 128, 100)          # K % 64
+    with pytest.raises(pp.PPError, match="not taken"):
+        pp.pp_op_gemm_tn(st, x.data_ptr(), 256, 64, 128, x.data_ptr(), 128, c.data_ptr(), 128, 128, 128, 128)       # blocks of 64 columns

@@ -52,13 +52,13 @@ int pp_op_gemm_nt_splitk_static(void* hip_stream, int dtype, const void* A_dev, 
 /* Causal softmax attention (Appendix "MHA with frozen heads", forward of every head; mask from the autoregressive
  * factorisation of Section 2.1).  qkv_dev: [B*S x 3*h*dh], columns q | k | v, head j at columns j*dh of each part
  * (q and k already rotated).  o_dev: [B*S x h*dh].  lse_dev: float [B*h*S], log-sum-exp of the scaled scores.
- * scratch_dev: 3 * B*h*dh*ceil(S/64)*64 bf16 elements, 16-byte aligned, used by the MFMA path (bf16, dh 64 or 128) for
- * transposed operand copies; NULL selects the plain kernels.  path as above. */
+ * scratch_dev: not used (the matrix-core kernels read q, k, v as stored); kept in the signature, may be NULL.
+ * path: 0 = automatic (MFMA kernels for bf16 with dh 64 or 128), 1 = plain kernels. */
 int pp_op_attention_fwd(void* hip_stream, int dtype, const void* qkv_dev, void* o_dev, float* lse_dev, void* scratch_dev,
                         int B, int S, int h, int dh, int path);
 
 /* Backward of the above for all heads: dqkv_dev [B*S x 3*h*dh] receives dq | dk | dv (in the rotated frame);
- * D_dev: float [B*h*S] scratch (row sums of dO * O). */
+ * D_dev: float [B*h*S], receives the row sums of dO * O.  scratch_dev: not used, may be NULL. */
 int pp_op_attention_bwd(void* hip_stream, int dtype, const void* qkv_dev, const void* o_dev, const float* lse_dev, const void* dO_dev,
                         void* dqkv_dev, float* D_dev, void* scratch_dev, int B, int S, int h, int dh, int path);
 

@@ -83,7 +83,7 @@ struct WsPlan {          // byte offsets into the workspace
   bool recompute;
   size_t a_x, a_n1, a_qkv, a_o, a_xm, a_n2, a_gu, a_a, a_rstd1, a_rstd2, a_lse;      // within a layer's block
   size_t xL, nf, rstdf, logits, rowloss, nvalid, dgpart;
-  size_t dx, dn, dA, dgu, dob, dqkv, Dattn, at;
+  size_t dx, dn, dA, dgu, dob, dqkv, Dattn;
   size_t fixed_end;      // everything above is mask independent
   size_t tA, tB, partial, partial_bytes, total;
   size_t act_bytes, shadow_bytes;
@@ -127,7 +127,6 @@ static WsPlan plan_ws(const pp_config& c, const Mask* mk) {
   p.rowloss = take(T * 4); p.nvalid = take(256); p.dgpart = take(64 * d * 4);
   p.dx = take(T * d * es); p.dn = take(T * d * es); p.dA = take(T * F * es); p.dgu = take(T * 2 * F * es);
   p.dob = take(T * d * es); p.dqkv = take(T * 3 * d * es); p.Dattn = take((size_t)c.max_batch * h * c.max_seq * 4);
-  p.at = take(c.dtype == PP_BF16 ? 3 * attn_scratch_elems(c.max_batch, c.max_seq, (int)h, (int)dh) * es : 0);
   p.fixed_end = off;
   // mask-dependent scratch for the weight-gradient GEMMs (operands transposed to K-contiguous form)
   Mask all{}; all.emb = all.norms = all.wo = all.lm = all.heads = all.ffn = true; all.fl = 0; all.fh = c.d_ff; all.hl = 0; all.hh = c.n_heads;
@@ -592,7 +591,7 @@ static void gemm_dw_tn(pp_model* m, const void* A, int lda, int m_blk, long a_bl
 static void attn_fwd(pp_model* m, const void* qkv, void* o, float* lse, int B, int S) {
   const int h = m->cfg.n_heads, dh = m->cfg.d_model / h;
   if (m->flop_acc) *m->flop_acc += 4.0 * ((double)B * S * (S + 1) / 2) * m->cfg.d_model;
-  if (m->cfg.dtype == PP_BF16 && !m->force_plain && k_attn_fwd_mfma(m->st, qkv, o, lse, m->wsp + m->ws.at, B, S, h, dh) == 0) { m->n_mfma++; return; }
+  if (m->cfg.dtype == PP_BF16 && !m->force_plain && k_attn_fwd_mfma(m->st, qkv, o, lse, B, S, h, dh) == 0) { m->n_mfma++; return; }
   m->n_plain++;
   k_attn_fwd_plain(m->st, m->cfg.dtype, qkv, o, lse, B, S, h, dh);
 }
@@ -602,7 +601,7 @@ static void attn_bwd(pp_model* m, const void* qkv, const void* o, const float* l
   const int h = m->cfg.n_heads, dh = m->cfg.d_model / h;
   if (m->flop_acc) *m->flop_acc += 8.0 * ((double)B * S * (S + 1) / 2) * m->cfg.d_model;
   if (m->cfg.dtype == PP_BF16 && !m->force_plain &&
-      k_attn_bwd_mfma(m->st, qkv, o, lse, dO, dqkv, Dbuf, m->wsp + m->ws.at, B, S, h, dh, cosb, sinb) == 0) { m->n_mfma++; return; }
+      k_attn_bwd_mfma(m->st, qkv, o, lse, dO, dqkv, Dbuf, B, S, h, dh, cosb, sinb) == 0) { m->n_mfma++; return; }
   m->n_plain++;
   k_attn_bwd_plain(m->st, m->cfg.dtype, qkv, o, lse, dO, dqkv, Dbuf, B, S, h, dh);
   k_rope(m->st, m->cfg.dtype, dqkv, cosb, sinb, B, S, h, dh, 1);
@@ -967,7 +966,7 @@ extern "C" int pp_op_attention_fwd(void* hip_stream, int dtype, const void* qkv,
   if (!qkv || !o || !lse) return fail(PP_EINVAL, "pp_op_attention_fwd: NULL pointer");
   if (int rc = check_attn(dtype, B, S, h, dh)) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
-  if (!(path == 0 && dtype == PP_BF16 && scratch && k_attn_fwd_mfma(st, qkv, o, lse, scratch, B, S, h, dh) == 0)) k_attn_fwd_plain(st, dtype, qkv, o, lse, B, S, h, dh);
+  if (!(path == 0 && dtype == PP_BF16 && k_attn_fwd_mfma(st, qkv, o, lse, B, S, h, dh) == 0)) k_attn_fwd_plain(st, dtype, qkv, o, lse, B, S, h, dh);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(PP_EHIP, std::string("pp_op_attention_fwd: ") + hipGetErrorString(e));
   return PP_OK;
@@ -977,7 +976,7 @@ extern "C" int pp_op_attention_bwd(void* hip_stream, int dtype, const void* qkv,
   if (!qkv || !o || !lse || !dO || !dqkv || !Dbuf) return fail(PP_EINVAL, "pp_op_attention_bwd: NULL pointer");
   if (int rc = check_attn(dtype, B, S, h, dh)) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
-  if (!(path == 0 && dtype == PP_BF16 && scratch && k_attn_bwd_mfma(st, qkv, o, lse, dO, dqkv, Dbuf, scratch, B, S, h, dh, nullptr, nullptr) == 0))
+  if (!(path == 0 && dtype == PP_BF16 && k_attn_bwd_mfma(st, qkv, o, lse, dO, dqkv, Dbuf, B, S, h, dh, nullptr, nullptr) == 0))
     k_attn_bwd_plain(st, dtype, qkv, o, lse, dO, dqkv, Dbuf, B, S, h, dh);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(PP_EHIP, std::string("pp_op_attention_bwd: ") + hipGetErrorString(e));

@@ -8,11 +8,13 @@
 //   dK,dV kernel:         S[query][key]   = Q K^T   -> lane column = key (its dK/dV row), 16 queries per lane
 // The 32x32 MFMA accumulator gives lane (l) the rows 8*(r/4) + 4*(l/32) + r%4 of column l%32.  Eight consecutive
 // accumulator registers therefore hold, for lane half h, the rows {4h..4h+3, 8+4h..8+4h+3} of a 16-row group: exactly
-// a valid K-operand of the next MFMA if the OTHER operand enumerates the contraction index in the same order.
-// That other operand always comes from a tensor stored "attention-transposed":
-//   AT(X)[(b*h + head)*dh + c][perm(s)] = X[b, s, head, c],   perm(s) = s with bits 2 and 3 swapped,
-// rows padded with zeros to a multiple of 64 positions.  With that layout one 16-byte LDS read yields the operand,
-// and P / dS never leave registers.
+// a valid K-operand of the next MFMA if the OTHER operand enumerates the contraction index in the same order, so P and
+// dS never leave registers.  That other operand is a [head-dim][position] slice of V, K, Q or dO, all of which are stored
+// position-major; it is gathered from the position-major LDS tile by the transpose read (ds_read_b64_tr_b16: within a
+// group of 16 lanes, lane i receives element i % 4 of the four 8-byte pieces addressed by lanes i/4, i/4+4, i/4+8,
+// i/4+12), one read for the positions 4h..4h+3 and one for 8+4h..8+4h+3.  The same tile serves the row-operand reads
+// (16 bytes = 8 consecutive head-dim elements of one position) of the score-shaped products, so every tensor is staged
+// once, in the layout it has in memory, and no transposed copies exist.
 #include "pp_kernels.h"
 #include "pp_dev.h"
 
@@ -22,6 +24,8 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
 
@@ -41,50 +45,18 @@ __device__ __forceinline__ void zero16(f32x16& v) {
   for (int r = 0; r < 16; ++r) v[r] = 0.f;
 }
 
-// ------------------------------------------------------------------------------------------ AT-layout transposes
-// src: rows = positions (ld_src elements apart), head `head` at columns col0 + head*dh; dst: AT layout, row length Sp.
-__global__ void head_transpose_kernel(const bf16_t* __restrict__ src, int ld_src, int col0, bf16_t* __restrict__ dst,
-                                      int S, int Sp, int h, int dh) {
-  __shared__ uint16_t tile[64][72];          // [position][column], rows 144 bytes apart (16-byte aligned)
-  const int s0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
-  const int bh = blockIdx.z, b = bh / h, head = bh % h;
-  const int t = threadIdx.x;
-  const uint16_t* sp = reinterpret_cast<const uint16_t*>(src) + (size_t)b * S * ld_src + col0 + (size_t)head * dh + c0;
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {          // 16-byte loads: 8 columns of one position
-    const int r = (t >> 3) + 32 * i, c8 = (t & 7) * 8;
-    uint4 v = make_uint4(0, 0, 0, 0);          // positions beyond S are stored as zeros
-    if (s0 + r < S) v = *reinterpret_cast<const uint4*>(sp + (size_t)(s0 + r) * ld_src + c8);
-    *reinterpret_cast<uint4*>(&tile[r][c8]) = v;
-  }
-  __syncthreads();
-  uint16_t* dp = reinterpret_cast<uint16_t*>(dst) + ((size_t)bh * dh + c0) * Sp + s0;
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {          // 16-byte stores: 8 destination slots of one column
-    const int c = (t >> 3) + 32 * i, p8 = (t & 7) * 8;
-    uint32_t w[4];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      // destination slot p holds source position perm(p) (bits 2 and 3 swapped)
-      const int pa = p8 + 2 * k, pb = pa + 1;
-      const int sa = (pa & ~12) | ((pa & 4) << 1) | ((pa & 8) >> 1), sb = (pb & ~12) | ((pb & 4) << 1) | ((pb & 8) >> 1);
-      w[k] = (uint32_t)tile[sa][c] | ((uint32_t)tile[sb][c] << 16);
-    }
-    *reinterpret_cast<uint4*>(dp + (size_t)c * Sp + p8) = make_uint4(w[0], w[1], w[2], w[3]);
-  }
-}
-static void head_transpose(hipStream_t st, const void* src, int ld_src, int col0, void* dst, int B, int S, int h, int dh) {
-  const int Sp = (S + 63) / 64 * 64;
-  dim3 grid(Sp / 64, dh / 64, B * h);
-  head_transpose_kernel<<<grid, 256, 0, st>>>((const bf16_t*)src, ld_src, col0, (bf16_t*)dst, S, Sp, h, dh);
-}
-
 // ------------------------------------------------------------------------------------------ tile staging helpers
-// A tile is ROWS x (CPR 16-byte chunks); chunk c of row r lives at r*CPR + (c ^ swz<CPR>(r)).  The swizzle makes the
-// 16 rows touched together by a 16-byte fragment read (same logical chunk) cover all 64 LDS banks once: with 128-byte
-// rows (CPR 8) rows r, r+1 differ in address bit 7 and (r >> 1) & 7 spreads the chunk; with 256-byte rows (CPR 16)
-// the row does not enter the bank index, so r & 15 spreads the chunk.  256 threads.
-template <int CPR> __device__ __forceinline__ int swz(int r) { return CPR == 8 ? ((r >> 1) & 7) : (r & 15); }
+// A tile is ROWS positions x (CPR 16-byte chunks of 8 head-dim elements); chunk c of row r lives at r*CPR + (c ^ swz<CPR>(r)).
+// The swizzle serves both kinds of read without bank conflicts (64 banks of 4 bytes):
+//   * row fragments (16 bytes, 16 consecutive rows at a time, same logical chunk) need 16 different 16-byte bank groups;
+//   * transpose reads (per phase 4 consecutive rows r = 4a .. 4a+3 x the 4 chunks 4q .. 4q+3 of a 32-column block) need
+//     the 4 rows in 4 different 64-byte groups.
+// 256-byte rows (CPR 16): the row does not enter the bank index; swz = (r & 3) << 2 | (r >> 2) & 3 is a bijection of r & 15
+// whose high half separates the 4 rows of a band.  128-byte rows (CPR 8): rows r, r+1 differ in address bit 7, rows r, r+2
+// do not; swz = (r & 2) << 1 | (r >> 2) & 3 is a bijection of bits 1..3 of r whose bit 2 separates rows r and r+2.
+template <int CPR> __device__ __forceinline__ int swz(int r) {
+  return CPR == 16 ? (((r & 3) << 2) | ((r >> 2) & 3)) : (((r & 2) << 1) | ((r >> 2) & 3));
+}
 #define PP_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define PP_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
 // Tiles go from global memory straight into LDS (global_load_lds_dwordx4: the 64 lanes' 16-byte pieces land at
@@ -129,6 +101,34 @@ template <int CPR>
 __device__ __forceinline__ bf16x8 frag(const u32x4* tile, int row, int chunk) {
   return __builtin_bit_cast(bf16x8, tile[row * CPR + (chunk ^ swz<CPR>(row))]);
 }
+// Transposed fragment: for head-dim column 32 colblk + lane % 32, the 8 positions row0 + {4h .. 4h+3, 8+4h .. 8+4h+3}
+// (h = lane / 32, row0 a multiple of 16) -- the order in which 8 consecutive accumulator registers enumerate a 16-row group.
+// Lane l = 16 grp + j points at row 4 (grp >> 1) + j / 4 of the band, 8-byte piece j % 4 of the 32-byte segment of column
+// half grp & 1.  tr_lane_off() is that address for column block 0 and row0 = 0; another column block flips bits 6..7 of it
+// (the block index enters the swizzled chunk by XOR), 8 rows further down flip bit 5 (bit 1 of the low swizzle field), and
+// row0 adds whole rows.  Tile bases are multiples of 8 KB (the kernels have no static LDS), so the XORs commute with them.
+template <int CPR>
+__device__ __forceinline__ uint32_t tr_lane_off(int lane) {
+  const int j = lane & 15, grp = lane >> 4;
+  const int r = 4 * (grp >> 1) + (j >> 2);          // row within the 16-row group (bit 3 clear)
+  const int chunk = 2 * (grp & 1) + ((j >> 1) & 1);
+  return (uint32_t)(r * (CPR * 16) + ((chunk ^ swz<CPR>(r)) << 4) + (j & 1) * 8);
+}
+__device__ __forceinline__ uint32_t lds_byte_offset(const void* p) { return (uint32_t)(uintptr_t)PP_LPTR(const_cast<void*>(p)); }
+// tl = byte offset of the tile in LDS + tr_lane_off()
+template <int CPR>
+__device__ __forceinline__ bf16x8 frag_tr(uint32_t tl, int row0, int colblk) {
+  typedef __attribute__((address_space(3))) s16x4* lptr;
+  const uint32_t lo = (tl ^ (uint32_t)(colblk << 6)) + (uint32_t)(row0 * CPR * 16);
+  const uint32_t hi = (tl ^ (uint32_t)((colblk << 6) | 32)) + (uint32_t)((row0 + 8) * CPR * 16);
+  const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(uintptr_t)lo);
+  const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(uintptr_t)hi);
+  const s16x8 v = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+  return __builtin_bit_cast(bf16x8, v);
+}
+// the same value, but opaque to the optimiser: address arithmetic that depends on it stays where it is written instead of
+// being hoisted out of the tile loop into registers that live across it
+__device__ __forceinline__ uint32_t launder(uint32_t v) { asm volatile("" : "+v"(v)); return v; }
 
 constexpr float LOG2E = 1.4426950408889634f, LN2 = 0.6931471805599453f;
 
@@ -167,17 +167,18 @@ __device__ __forceinline__ void causal_block_map(int id, int n_pairs, int n_blk,
 // ------------------------------------------------------------------------------------------ forward
 // B*h*ceil(S/128) workgroups (see causal_block_map), 256 threads: wave w owns queries q0 + 32w .. +31; KV tiles of 64 keys.
 template <int DH>
-__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ vt,
-                                                           bf16_t* __restrict__ o, float* __restrict__ lse, int S, int Sp, int h, int n_pairs, int n_blk) {
+__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o, float* __restrict__ lse, int S, int h,
+                                                           int n_pairs, int n_blk) {
   constexpr int KS = DH / 16, CT = DH / 32, CPRK = DH / 8;
   constexpr int CH = 4;          // fragment reads (= MFMAs) per fence; divides 2 KS and 4 CT
   extern __shared__ u32x4 lds[];
-  constexpr int K_CH = 64 * CPRK, V_CH = DH * 8, ST_CH = K_CH + V_CH;
+  constexpr int K_CH = 64 * CPRK, ST_CH = 2 * K_CH;          // a stage = K rows, then V rows, of 64 keys
   const int d = h * DH, ld = 3 * d;
   int pair, comb;
   causal_block_map(blockIdx.x, n_pairs, (n_blk + 1) / 2, pair, comb);
   const int head = pair % h, b = pair / h;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), l32 = lane & 31, lh = lane >> 5;
+  const uint32_t tr_off = tr_lane_off<CPRK>(lane);
   // a late (heavy) query block, then its early (light) mirror image: every workgroup costs the same
   for (int part = 0; part < 2; ++part) {
     const int qblk = part == 0 ? n_blk - 1 - comb : comb;
@@ -185,7 +186,6 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
     const int q0 = qblk * 128, qw0 = q0 + wave * 32;
     const int q = qw0 + l32;
     const bf16_t* base = qkv + (size_t)b * S * ld + (size_t)head * DH;
-    const bf16_t* vtb = vt + ((size_t)(b * h + head) * DH) * Sp;
     const int n_tiles = min((q0 + 128 + 63) / 64, (S + 63) / 64);
 
     bf16x8 qf[KS];
@@ -201,9 +201,9 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
     const float sc2 = LOG2E / sqrtf((float)DH);
 
     auto ksrc = [&](int kv0) { return [=](int row, int c) { return base + (size_t)min(kv0 + row, S - 1) * ld + d + c * 8; }; };
-    auto vsrc = [&](int kv0) { return [=](int row, int c) { return vtb + (size_t)row * Sp + kv0 + c * 8; }; };
+    auto vsrc = [&](int kv0) { return [=](int row, int c) { return base + (size_t)min(kv0 + row, S - 1) * ld + 2 * d + c * 8; }; };
     Stage<64, CPRK>::issue(lds, wave, lane, ksrc(0));
-    Stage<DH, 8>::issue(lds + K_CH, wave, lane, vsrc(0));
+    Stage<64, CPRK>::issue(lds + K_CH, wave, lane, vsrc(0));
     stage_sync();
 
     for (int j = 0; j < n_tiles; ++j) {
@@ -212,14 +212,15 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
       u32x4* nxt = lds + ((j + 1) & 1) * ST_CH;
       const int kv0 = j * 64, kvn = min(j + 1, n_tiles - 1) * 64;
       Stage<64, CPRK>::issue(nxt, wave, lane, ksrc(kvn));
-      Stage<DH, 8>::issue(nxt + K_CH, wave, lane, vsrc(kvn));
+      Stage<64, CPRK>::issue(nxt + K_CH, wave, lane, vsrc(kvn));
       __builtin_amdgcn_sched_barrier(0);
       if (kv0 <= qw0 + 31) {          // wave-uniform: some key of the tile is visible to some query of this wave
         f32x16 sacc[2];
         zero16(sacc[0]); zero16(sacc[1]);
         // MFMA steps n = 0 .. 2 KS - 1: key rows (n & 1) * 32.., head-dim slice n >> 1; CH steps per fence
         auto fragK = [&](int n) { return frag<CPRK>(kt, (n & 1) * 32 + l32, 2 * (n >> 1) + lh); };
-        auto fragV = [&](int n) { return frag<8>(vtile, (n % CT) * 32 + l32, 2 * (n / CT) + lh); };
+        const uint32_t vtl = lds_byte_offset(vtile) + tr_off;
+        auto fragV = [&](int n) { return frag_tr<CPRK>(vtl, 16 * (n / CT), n % CT); };          // V^T block n % CT, keys 16 (n / CT) ..
         {
           bf16x8 kb[2][CH];
 #pragma unroll
@@ -294,7 +295,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
               const int n = c * CH + i;
               oacc[n % CT] = MFMA(vb[c & 1][i], pf[n / CT], oacc[n % CT]);
             }
-            PP_READS_THEN_MFMAS(CH, CH);
+            PP_READS_THEN_MFMAS(2 * CH, CH);
           }
         }
       }
@@ -347,20 +348,23 @@ __device__ __forceinline__ void unrotate_tile(f32x16 (&acc)[DH / 32], const floa
 // ------------------------------------------------------------------------------------------ backward: dQ
 // B*h*ceil(S/256) workgroups (see causal_block_map), 512 threads = 8 waves (2 per SIMD, <= 256 registers each, so every MFMA keeps its
 // accumulator in ordinary VGPRs): wave w owns queries q0 + 32w .. +31.  Per KV tile of 64 keys, in two groups of 32:
-// S^T = K Q^T, dP^T = V dO^T, dS^T = P^T * (dP^T - D), dQ^T += AT(K) dS^T.
+// S^T = K Q^T, dP^T = V dO^T, dS^T = P^T * (dP^T - D), dQ^T += K^T dS^T (K^T gathered from the K rows by transpose reads).
+// The kernel also forms D = rowsum(dO * O) for its queries (each lane already holds half of its query's dO row) and
+// stores it in Dbuf for the dK/dV kernel, which runs after it.
 template <int DH>
-__global__ __launch_bounds__(512, 2) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ kt_at,
+__global__ __launch_bounds__(512, 2) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ o,
                                                               const bf16_t* __restrict__ dO, const float* __restrict__ lse,
-                                                              const float* __restrict__ Dbuf, bf16_t* __restrict__ dqkv, int S, int Sp, int h, int n_pairs, int n_blk,
+                                                              float* __restrict__ Dbuf, bf16_t* __restrict__ dqkv, int S, int h, int n_pairs, int n_blk,
                                                               const float* __restrict__ cosb, const float* __restrict__ sinb) {
   constexpr int KS = DH / 16, CT = DH / 32, CPRK = DH / 8, NW = 8;
   extern __shared__ u32x4 lds[];
-  constexpr int K_CH = 64 * CPRK, T_CH = DH * 8, ST_CH = 2 * K_CH + T_CH;
+  constexpr int K_CH = 64 * CPRK, ST_CH = 2 * K_CH;          // a stage = K rows, then V rows, of 64 keys
   const int d = h * DH, ld = 3 * d;
   int pair, comb;
   causal_block_map(blockIdx.x, n_pairs, (n_blk + 1) / 2, pair, comb);
   const int head = pair % h, b = pair / h;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), l32 = lane & 31, lh = lane >> 5;
+  const uint32_t tr_off = tr_lane_off<CPRK>(lane);
   // a late (heavy) query block, then its early (light) mirror image: every workgroup costs the same
   for (int part = 0; part < 2; ++part) {
     const int qblk = part == 0 ? n_blk - 1 - comb : comb;
@@ -368,33 +372,40 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dq_kernel(const bf16_t* __res
     const int q0 = qblk * 256, qw0 = q0 + wave * 32;
     const int q = qw0 + l32, qc = min(q, S - 1);
     const bf16_t* base = qkv + (size_t)b * S * ld + (size_t)head * DH;
-    const bf16_t* ktb = kt_at + ((size_t)(b * h + head) * DH) * Sp;
     const int n_tiles = min((q0 + 256 + 63) / 64, (S + 63) / 64);
     const float scale = 1.0f / sqrtf((float)DH), sc2 = LOG2E * scale;
 
     bf16x8 qf[KS], dof[KS];
+    float Dq = 0.f;          // D of this lane's query: sum over the head dim of dO * O, lane halves hold alternate 8-element pieces
     {
       const bf16_t* qp = base + (size_t)qc * ld + 8 * lh;
       const bf16_t* dp = dO + ((size_t)b * S + qc) * d + (size_t)head * DH + 8 * lh;
+      const bf16_t* op = o + ((size_t)b * S + qc) * d + (size_t)head * DH + 8 * lh;
 #pragma unroll
       for (int s = 0; s < KS; ++s) {
         qf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qp + 16 * s));
-        dof[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(dp + 16 * s));
+        const u32x4 dw = *reinterpret_cast<const u32x4*>(dp + 16 * s), ow = *reinterpret_cast<const u32x4*>(op + 16 * s);
+        dof[s] = __builtin_bit_cast(bf16x8, dw);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          Dq = fmaf(__uint_as_float(dw[e] << 16), __uint_as_float(ow[e] << 16), Dq);
+          Dq = fmaf(__uint_as_float(dw[e] & 0xffff0000u), __uint_as_float(ow[e] & 0xffff0000u), Dq);
+        }
       }
     }
+    Dq += __shfl_xor(Dq, 32, 64);
     const size_t stat = ((size_t)b * h + head) * S + qc;
-    const float nlse2 = -lse[stat] * LOG2E, Dq = Dbuf[stat];
+    if (lh == 0 && q < S) Dbuf[stat] = Dq;
+    const float nlse2 = -lse[stat] * LOG2E;
     f32x16 dqacc[CT];
 #pragma unroll
     for (int c = 0; c < CT; ++c) zero16(dqacc[c]);
 
     auto ksrc = [&](int kv0) { return [=](int row, int c) { return base + (size_t)min(kv0 + row, S - 1) * ld + d + c * 8; }; };
     auto vsrc = [&](int kv0) { return [=](int row, int c) { return base + (size_t)min(kv0 + row, S - 1) * ld + 2 * d + c * 8; }; };
-    auto tsrc = [&](int kv0) { return [=](int row, int c) { return ktb + (size_t)row * Sp + kv0 + c * 8; }; };
     auto issue_all = [&](u32x4* stage, int kv0) {
       Stage<64, CPRK, NW>::issue(stage, wave, lane, ksrc(kv0));
       Stage<64, CPRK, NW>::issue(stage + K_CH, wave, lane, vsrc(kv0));
-      Stage<DH, 8, NW>::issue(stage + 2 * K_CH, wave, lane, tsrc(kv0));
     };
     issue_all(lds, 0);
     stage_sync();
@@ -402,7 +413,6 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dq_kernel(const bf16_t* __res
     for (int j = 0; j < n_tiles; ++j) {
       const u32x4* ktile = lds + (j & 1) * ST_CH;
       const u32x4* vtile = ktile + K_CH;
-      const u32x4* ttile = ktile + 2 * K_CH;
       u32x4* nxt = lds + ((j + 1) & 1) * ST_CH;
       const int kv0 = j * 64, kvn = min(j + 1, n_tiles - 1) * 64;
       issue_all(nxt, kvn);
@@ -444,22 +454,24 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dq_kernel(const bf16_t* __res
         dsf[0] = pack8(sacc, 0); dsf[1] = pack8(sacc, 8);
         {
           __builtin_amdgcn_sched_barrier(0);
-          bf16x8 tb[2];
-          tb[0] = frag<8>(ttile, l32, 2 * (2 * mt) + lh);
-          tb[1] = frag<8>(ttile, (1 % CT) * 32 + l32, 2 * (2 * mt + 1 / CT) + lh);
+          bf16x8 tb[2];          // K^T block n % CT for the 16 keys 32 mt + 16 (n / CT) ..
+          const uint32_t ktl = launder(lds_byte_offset(ktile) + tr_off);
+          tb[0] = frag_tr<CPRK>(ktl, 32 * mt, 0);
+          tb[1] = frag_tr<CPRK>(ktl, 32 * mt + 16 * (1 / CT), 1 % CT);
 #pragma unroll
           for (int sp = 0; sp < CT; ++sp) {          // two (u, c) steps per fence
             PP_STEP_BEGIN();
             bf16x8 cur0 = tb[0], cur1 = tb[1];
             if (sp + 1 < CT) {
               const int n0 = 2 * sp + 2, n1 = 2 * sp + 3;
-              tb[0] = frag<8>(ttile, (n0 % CT) * 32 + l32, 2 * (2 * mt + n0 / CT) + lh);
-              tb[1] = frag<8>(ttile, (n1 % CT) * 32 + l32, 2 * (2 * mt + n1 / CT) + lh);
+              const uint32_t kt2 = launder(ktl);
+              tb[0] = frag_tr<CPRK>(kt2, 32 * mt + 16 * (n0 / CT), n0 % CT);
+              tb[1] = frag_tr<CPRK>(kt2, 32 * mt + 16 * (n1 / CT), n1 % CT);
             }
             const int a0 = 2 * sp, a1 = 2 * sp + 1;
             dqacc[a0 % CT] = MFMA(cur0, dsf[a0 / CT], dqacc[a0 % CT]);
             dqacc[a1 % CT] = MFMA(cur1, dsf[a1 / CT], dqacc[a1 % CT]);
-            PP_READS_THEN_MFMAS(2, 2);
+            PP_READS_THEN_MFMAS(4, 2);
           }
         }
       }
@@ -485,32 +497,32 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dq_kernel(const bf16_t* __res
 // ------------------------------------------------------------------------------------------ backward: dK, dV
 // B*h*ceil(S/128) workgroups (see causal_block_map), 512 threads = 8 waves.  Waves w and w+4 own the same 32 keys k0 + 32(w&3) .. +31 (lane
 // column = key) and split the WORK, not the data: wave w ("V-wave") forms S = Q K^T and P = exp(S - lse), hands P
-// (bf16, in MFMA operand order) to its partner through an LDS mailbox and accumulates dV^T += AT(dO) P; wave
-// w+4 ("K-wave") forms dP = dO V^T, picks P up, forms dS = P * (dP - D) and accumulates dK^T += AT(Q) dS.
+// (bf16, in MFMA operand order) to its partner through an LDS mailbox and accumulates dV^T += dO^T P; wave
+// w+4 ("K-wave") forms dP = dO V^T, picks P up, forms dS = P * (dP - D) and accumulates dK^T += Q^T dS (dO^T and Q^T
+// are gathered from the staged dO and Q rows by transpose reads).
 // Nothing is computed twice, each wave carries one 32 x dh accumulator, and everything stays in VGPRs.
 // Query tiles of 64 run from the diagonal to the end of the sequence.  The K-waves run ONE TILE BEHIND the V-waves:
-// in iteration i the V-waves work on tile i (rows of Q, AT(dO)) and fill mailbox i % 2 while the K-waves work on tile
-// i-1 (rows of dO, AT(Q)) and empty mailbox (i-1) % 2, so the two waves that share a SIMD never wait for each other
-// inside an iteration -- one's exponentials overlap the other's matrix work -- and one barrier per tile is enough.
-// LDS: two "V sets" (Q rows + AT(dO)), two "K sets" (dO rows + AT(Q)), two mailboxes: 160 KB at dh = 128.
+// in iteration i the V-waves work on tile i and fill mailbox i % 2 while the K-waves work on tile i-1 and empty mailbox
+// (i-1) % 2, so the two waves that share a SIMD never wait for each other inside an iteration -- one's exponentials
+// overlap the other's matrix work -- and one barrier per tile is enough.
+// LDS: a ring of three tile sets (Q rows + dO rows of 64 queries; both roles read both tiles, tile i+1 is in flight while
+// tiles i and i-1 are in use) and two mailboxes: 128 KB at dh = 128.
 // The per-query statistics (log-sum-exp for the V-waves, D for the K-waves) go straight from global memory into
 // registers, one tile ahead.
 template <int DH, bool kwave>          // kwave false: V-wave (S, P, dV)   true: K-wave (dP, dS, dK)
-__device__ __forceinline__ void attn_bwd_dkv_part(u32x4* lds, const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ qt_at,
-                                                  const bf16_t* __restrict__ dO, const bf16_t* __restrict__ dot_at,
+__device__ __forceinline__ void attn_bwd_dkv_part(u32x4* lds, const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO,
                                                   const float* __restrict__ lse, const float* __restrict__ Dbuf, bf16_t* __restrict__ dqkv,
-                                                  int S, int Sp, int h, int stats_vec, int head, int b, int kblk, int lane, int wave,
+                                                  int S, int h, int stats_vec, int head, int b, int kblk, int lane, int wave,
                                                   const float* __restrict__ cosb, const float* __restrict__ sinb) {
   constexpr int KS = DH / 16, CT = DH / 32, CPRK = DH / 8, NW = 8;
-  constexpr int R_CH = 64 * CPRK, T_CH = DH * 8, SET_CH = R_CH + T_CH;
-  constexpr int MAIL_CH = 2 * 4 * 2 * 64, MAIL0 = 4 * SET_CH;          // mailbox: [query group 2][key group 4][fragment 2][lane 64] chunks
+  constexpr int R_CH = 64 * CPRK, SET_CH = 2 * R_CH;          // a set = Q rows, then dO rows, of 64 queries
+  constexpr int MAIL_CH = 2 * 4 * 2 * 64, MAIL0 = 3 * SET_CH;          // mailbox: [query group 2][key group 4][fragment 2][lane 64] chunks
   const int d = h * DH, ld = 3 * d;
   const int l32 = lane & 31, lh = lane >> 5, kg = wave & 3;
+  const uint32_t tr_off = tr_lane_off<CPRK>(lane);
   const int k0 = kblk * 128, kw0 = k0 + kg * 32;
   const int key = kw0 + l32, keyc = min(key, S - 1);
   const bf16_t* base = qkv + (size_t)b * S * ld + (size_t)head * DH;
-  const bf16_t* qtb = qt_at + ((size_t)(b * h + head) * DH) * Sp;
-  const bf16_t* dotb = dot_at + ((size_t)(b * h + head) * DH) * Sp;
   const bf16_t* dob = dO + (size_t)b * S * d + (size_t)head * DH;
   const float* statb = (kwave ? Dbuf : lse) + ((size_t)b * h + head) * S;
   const int t_first = k0 / 64, n_tiles = (S + 63) / 64 - t_first;
@@ -528,15 +540,10 @@ __device__ __forceinline__ void attn_bwd_dkv_part(u32x4* lds, const bf16_t* __re
   for (int c = 0; c < CT; ++c) zero16(oacc[c]);
 
   // sources as wave-uniform tile base + per-lane byte offset; rows past the end of the sequence repeat the last row
-  auto issue_v = [&](u32x4* set, int qq0) {
+  auto issue_set = [&](u32x4* set, int qq0) {
     const int lim = S - 1 - qq0;
     Stage<64, CPRK, NW>::issue_u(set, wave, lane, base + (size_t)qq0 * ld, [=](int row, int c) { return (uint32_t)(min(row, lim) * ld + c * 8) * 2u; });
-    Stage<DH, 8, NW>::issue_u(set + R_CH, wave, lane, dotb, [=](int row, int c) { return (uint32_t)(row * Sp + qq0 + c * 8) * 2u; });
-  };
-  auto issue_k = [&](u32x4* set, int qq0) {
-    const int lim = S - 1 - qq0;
-    Stage<64, CPRK, NW>::issue_u(set, wave, lane, dob + (size_t)qq0 * d, [=](int row, int c) { return (uint32_t)(min(row, lim) * d + c * 8) * 2u; });
-    Stage<DH, 8, NW>::issue_u(set + R_CH, wave, lane, qtb, [=](int row, int c) { return (uint32_t)(row * Sp + qq0 + c * 8) * 2u; });
+    Stage<64, CPRK, NW>::issue_u(set + R_CH, wave, lane, dob + (size_t)qq0 * d, [=](int row, int c) { return (uint32_t)(min(row, lim) * d + c * 8) * 2u; });
   };
   // statistics of this lane's 2 x 16 accumulator rows for the wave's next tile (rows past the end: any finite value)
   float st[2][16];
@@ -562,21 +569,20 @@ __device__ __forceinline__ void attn_bwd_dkv_part(u32x4* lds, const bf16_t* __re
     }
   };
 
-  issue_v(lds, t_first * 64);
+  issue_set(lds, t_first * 64);
   load_stats(t_first * 64);          // first tile of either role
   stage_sync();
 
   for (int it = 0; it <= n_tiles; ++it) {
     const int qv0 = (t_first + it) * 64;          // the V-waves' tile; the K-waves work on the one before it
-    if (it + 1 < n_tiles) issue_v(lds + ((it + 1) & 1) * SET_CH, qv0 + 64);          // last read in iteration it-1
-    if (it < n_tiles) issue_k(lds + (2 + (it & 1)) * SET_CH, qv0);                    // last read in iteration it-1
+    if (it + 1 < n_tiles) issue_set(lds + ((it + 1) % 3) * SET_CH, qv0 + 64);          // ring slot of tile it-2, last read in iteration it-1
     __builtin_amdgcn_sched_barrier(0);
     const int my_it = kwave ? it - 1 : it;          // index of the tile this wave works on now
     const int qq0 = (t_first + my_it) * 64;
     if (my_it >= 0 && my_it < n_tiles && qq0 + 63 >= kw0) {          // wave-uniform: some query of the tile sees some key of the wave
-      const u32x4* set = lds + ((kwave ? 2 : 0) + (my_it & 1)) * SET_CH;
-      const u32x4* rows_tile = set;                   // Q rows (V-wave) or dO rows (K-wave)
-      const u32x4* at_tile = set + R_CH;              // AT(dO) (V-wave) or AT(Q) (K-wave)
+      const u32x4* set = lds + (my_it % 3) * SET_CH;
+      const u32x4* rows_tile = set + (kwave ? R_CH : 0);          // row operand: Q rows (V-wave) or dO rows (K-wave)
+      const u32x4* tr_tile = set + (kwave ? 0 : R_CH);            // transposed operand: dO rows (V-wave) or Q rows (K-wave)
       u32x4* mail = lds + MAIL0 + (my_it & 1) * MAIL_CH + (kg * 2) * 64 + lane;          // + mt * 512 + fragment * 64
       // The accumulators start from the row statistics instead of zero, so the products come out as S - lse / scale
       // (V-wave) or dP - D (K-wave) and the statistics need no registers while the tile is worked on.
@@ -643,21 +649,23 @@ __device__ __forceinline__ void attn_bwd_dkv_part(u32x4* lds, const bf16_t* __re
       {          // oacc[c] += AT tile rows c*32.., 16-query slice u  x  opf[u]; steps run over (u, c) with c fastest
         __builtin_amdgcn_sched_barrier(0);
         bf16x8 tb[2];
-        tb[0] = frag<8>(at_tile, l32, lh);
-        tb[1] = frag<8>(at_tile, (1 % CT) * 32 + l32, 2 * (1 / CT) + lh);
+        const uint32_t ttl = launder(lds_byte_offset(tr_tile) + tr_off);
+        tb[0] = frag_tr<CPRK>(ttl, 0, 0);
+        tb[1] = frag_tr<CPRK>(ttl, 16 * (1 / CT), 1 % CT);
 #pragma unroll
         for (int sp = 0; sp < 2 * CT; ++sp) {          // two (u, c) steps per fence
           PP_STEP_BEGIN();
           bf16x8 cur0 = tb[0], cur1 = tb[1];
           if (sp + 1 < 2 * CT) {
             const int n0 = 2 * sp + 2, n1 = 2 * sp + 3;
-            tb[0] = frag<8>(at_tile, (n0 % CT) * 32 + l32, 2 * (n0 / CT) + lh);
-            tb[1] = frag<8>(at_tile, (n1 % CT) * 32 + l32, 2 * (n1 / CT) + lh);
+            const uint32_t tt2 = launder(ttl);
+            tb[0] = frag_tr<CPRK>(tt2, 16 * (n0 / CT), n0 % CT);
+            tb[1] = frag_tr<CPRK>(tt2, 16 * (n1 / CT), n1 % CT);
           }
           const int a0 = 2 * sp, a1 = 2 * sp + 1;
           oacc[a0 % CT] = MFMA(cur0, opf[a0 / CT], oacc[a0 % CT]);
           oacc[a1 % CT] = MFMA(cur1, opf[a1 / CT], oacc[a1 % CT]);
-          PP_READS_THEN_MFMAS(2, 2);
+          PP_READS_THEN_MFMAS(4, 2);
         }
       }
     }
@@ -684,10 +692,9 @@ __device__ __forceinline__ void attn_bwd_dkv_part(u32x4* lds, const bf16_t* __re
 // The two roles are separate instantiations of the tile loop (their loop-invariant registers differ); both cross the
 // same number of barriers.
 template <int DH>
-__global__ __launch_bounds__(512, 2) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ qt_at,
-                                                               const bf16_t* __restrict__ dO, const bf16_t* __restrict__ dot_at,
+__global__ __launch_bounds__(512, 2) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO,
                                                                const float* __restrict__ lse, const float* __restrict__ Dbuf,
-                                                               bf16_t* __restrict__ dqkv, int S, int Sp, int h, int stats_vec, int n_pairs, int n_blk,
+                                                               bf16_t* __restrict__ dqkv, int S, int h, int stats_vec, int n_pairs, int n_blk,
                                                                const float* __restrict__ cosb, const float* __restrict__ sinb) {
   extern __shared__ u32x4 lds[];
   int pair, comb;
@@ -698,8 +705,8 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkv_kernel(const bf16_t* __re
   for (int part = 0; part < 2; ++part) {
     const int kblk = part == 0 ? comb : n_blk - 1 - comb;
     if (part == 1 && kblk == comb) break;
-    if (wave >= 4) attn_bwd_dkv_part<DH, true>(lds, qkv, qt_at, dO, dot_at, lse, Dbuf, dqkv, S, Sp, h, stats_vec, head, b, kblk, lane, wave, cosb, sinb);
-    else attn_bwd_dkv_part<DH, false>(lds, qkv, qt_at, dO, dot_at, lse, Dbuf, dqkv, S, Sp, h, stats_vec, head, b, kblk, lane, wave, cosb, sinb);
+    if (wave >= 4) attn_bwd_dkv_part<DH, true>(lds, qkv, dO, lse, Dbuf, dqkv, S, h, stats_vec, head, b, kblk, lane, wave, cosb, sinb);
+    else attn_bwd_dkv_part<DH, false>(lds, qkv, dO, lse, Dbuf, dqkv, S, h, stats_vec, head, b, kblk, lane, wave, cosb, sinb);
   }
 }
 
@@ -709,55 +716,46 @@ static bool set_lds(K kern, int bytes) {
   return hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, bytes) == hipSuccess;
 }
 
-size_t attn_scratch_elems(int B, int S, int h, int dh) { return (size_t)B * h * dh * ((S + 63) / 64 * 64); }
-
 template <int DH>
-static int fwd_launch(hipStream_t st, const void* qkv, void* o, float* lse, void* at0, int B, int S, int h) {
-  static bool ok = set_lds(attn_fwd_kernel<DH>, 2 * (64 * (DH / 8) + DH * 8) * 16);
+static int fwd_launch(hipStream_t st, const void* qkv, void* o, float* lse, int B, int S, int h) {
+  constexpr int FWD_LDS = 2 * (2 * 64 * (DH / 8)) * 16;          // two stages of K rows + V rows
+  static bool ok = set_lds(attn_fwd_kernel<DH>, FWD_LDS);
   if (!ok) return 1;
-  const int Sp = (S + 63) / 64 * 64, d = h * DH;
-  head_transpose(st, qkv, 3 * d, 2 * d, at0, B, S, h, DH);          // AT(V)
   const int n_blk = (S + 127) / 128;
-  attn_fwd_kernel<DH><<<dim3(B * h * ((n_blk + 1) / 2)), 256, 2 * (64 * (DH / 8) + DH * 8) * 16, st>>>((const bf16_t*)qkv, (const bf16_t*)at0, (bf16_t*)o, lse, S, Sp, h,
-                                                                                           B * h, n_blk);
+  attn_fwd_kernel<DH><<<dim3(B * h * ((n_blk + 1) / 2)), 256, FWD_LDS, st>>>((const bf16_t*)qkv, (bf16_t*)o, lse, S, h, B * h, n_blk);
   return 0;
 }
 template <int DH>
 static int bwd_launch(hipStream_t st, const void* qkv, const void* o, const float* lse, const void* dO, void* dqkv, float* Dbuf,
-                      void* at0, void* at1, void* at2, int B, int S, int h, const float* cosb, const float* sinb) {
-  constexpr int DQ_LDS = 2 * (2 * 64 * (DH / 8) + DH * 8) * 16;
-  constexpr int DKV_LDS = (4 * (64 * (DH / 8) + DH * 8) + 2 * (2 * 4 * 2 * 64)) * 16;          // two V sets, two K sets, two P mailboxes
+                      int B, int S, int h, const float* cosb, const float* sinb) {
+  constexpr int DQ_LDS = 2 * (2 * 64 * (DH / 8)) * 16;                                   // two stages of K rows + V rows
+  constexpr int DKV_LDS = (3 * (2 * 64 * (DH / 8)) + 2 * (2 * 4 * 2 * 64)) * 16;          // three sets of Q rows + dO rows, two P mailboxes
   static bool ok = set_lds(attn_bwd_dq_kernel<DH>, DQ_LDS) && set_lds(attn_bwd_dkv_kernel<DH>, DKV_LDS);
   if (!ok) return 1;
-  const int Sp = (S + 63) / 64 * 64, d = h * DH;
-  k_attn_D(st, 1, o, dO, Dbuf, B, S, h, DH);
-  head_transpose(st, qkv, 3 * d, d, at0, B, S, h, DH);          // AT(K)
-  head_transpose(st, qkv, 3 * d, 0, at1, B, S, h, DH);          // AT(Q)
-  head_transpose(st, dO, d, 0, at2, B, S, h, DH);               // AT(dO)
   const int nb_kv = (S + 127) / 128, nb_dq = (S + 255) / 256;
   const int stats_vec = (S % 4 == 0) && ((reinterpret_cast<uintptr_t>(lse) | reinterpret_cast<uintptr_t>(Dbuf)) & 15) == 0;          // 16-byte loads of lse / D
-  attn_bwd_dq_kernel<DH><<<dim3(B * h * ((nb_dq + 1) / 2)), 512, DQ_LDS, st>>>((const bf16_t*)qkv, (const bf16_t*)at0, (const bf16_t*)dO, lse, Dbuf, (bf16_t*)dqkv, S, Sp, h,
+  // the dQ kernel also writes D = rowsum(dO * O), which the dK/dV kernel then reads
+  attn_bwd_dq_kernel<DH><<<dim3(B * h * ((nb_dq + 1) / 2)), 512, DQ_LDS, st>>>((const bf16_t*)qkv, (const bf16_t*)o, (const bf16_t*)dO, lse, Dbuf, (bf16_t*)dqkv, S, h,
                                                                  B * h, nb_dq, cosb, sinb);
-  attn_bwd_dkv_kernel<DH><<<dim3(B * h * ((nb_kv + 1) / 2)), 512, DKV_LDS, st>>>((const bf16_t*)qkv, (const bf16_t*)at1, (const bf16_t*)dO, (const bf16_t*)at2, lse, Dbuf,
-                                                      (bf16_t*)dqkv, S, Sp, h, stats_vec, B * h, nb_kv, cosb, sinb);
+  attn_bwd_dkv_kernel<DH><<<dim3(B * h * ((nb_kv + 1) / 2)), 512, DKV_LDS, st>>>((const bf16_t*)qkv, (const bf16_t*)dO, lse, Dbuf,
+                                                      (bf16_t*)dqkv, S, h, stats_vec, B * h, nb_kv, cosb, sinb);
   return 0;
 }
 
-// scratch: 3 * attn_scratch_elems(B,S,h,dh) bf16 elements (AT-layout copies), 16-byte aligned
-int k_attn_fwd_mfma(hipStream_t st, const void* qkv, void* o, float* lse, void* scratch, int B, int S, int h, int dh) {
-  if (!scratch || (dh != 64 && dh != 128) || S < 1) return 1;
-  return dh == 64 ? fwd_launch<64>(st, qkv, o, lse, scratch, B, S, h) : fwd_launch<128>(st, qkv, o, lse, scratch, B, S, h);
+// bf16, head dim 64 or 128, 16-byte aligned operands with row strides that are multiples of 8 elements
+int k_attn_fwd_mfma(hipStream_t st, const void* qkv, void* o, float* lse, int B, int S, int h, int dh) {
+  if ((dh != 64 && dh != 128) || S < 1) return 1;
+  if (((uintptr_t)qkv | (uintptr_t)o) & 15) return 1;
+  return dh == 64 ? fwd_launch<64>(st, qkv, o, lse, B, S, h) : fwd_launch<128>(st, qkv, o, lse, B, S, h);
 }
 // rope_cos / rope_sin ([S x dh/2] fp32, both or neither): dq and dk are returned with respect to the UN-rotated q and k
-// (the inverse rotation is applied to the accumulators before they are stored)
+// (the inverse rotation is applied to the accumulators before they are stored).  Dbuf receives rowsum(dO * O).
 int k_attn_bwd_mfma(hipStream_t st, const void* qkv, const void* o, const float* lse, const void* dO, void* dqkv, float* Dbuf,
-                    void* scratch, int B, int S, int h, int dh, const float* rope_cos, const float* rope_sin) {
-  if (!scratch || (dh != 64 && dh != 128) || S < 1 || (rope_cos == nullptr) != (rope_sin == nullptr)) return 1;
-  if (((uintptr_t)rope_cos | (uintptr_t)rope_sin) & 15) return 1;
-  const size_t n = attn_scratch_elems(B, S, h, dh);
-  bf16_t* s0 = (bf16_t*)scratch;
-  return dh == 64 ? bwd_launch<64>(st, qkv, o, lse, dO, dqkv, Dbuf, s0, s0 + n, s0 + 2 * n, B, S, h, rope_cos, rope_sin)
-                  : bwd_launch<128>(st, qkv, o, lse, dO, dqkv, Dbuf, s0, s0 + n, s0 + 2 * n, B, S, h, rope_cos, rope_sin);
+                    int B, int S, int h, int dh, const float* rope_cos, const float* rope_sin) {
+  if ((dh != 64 && dh != 128) || S < 1 || (rope_cos == nullptr) != (rope_sin == nullptr)) return 1;
+  if (((uintptr_t)rope_cos | (uintptr_t)rope_sin | (uintptr_t)qkv | (uintptr_t)o | (uintptr_t)dO | (uintptr_t)dqkv) & 15) return 1;
+  return dh == 64 ? bwd_launch<64>(st, qkv, o, lse, dO, dqkv, Dbuf, B, S, h, rope_cos, rope_sin)
+                  : bwd_launch<128>(st, qkv, o, lse, dO, dqkv, Dbuf, B, S, h, rope_cos, rope_sin);
 }
 
 }  // namespace pp

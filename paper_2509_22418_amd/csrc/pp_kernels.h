@@ -83,11 +83,10 @@ int k_gemm_tn_mfma(hipStream_t st, const void* A, int lda, int m_blk, long a_blk
                    int M, int N, int K, int splits, float* partial);
 void gemm_set_variant(int v);          // 0: register-staged MFMA GEMM, 1: direct-to-LDS MFMA GEMM
 void gemm_set_persistent(int v);       // 1 (default): a workgroup per compute unit walks several tiles when there are more tiles than units
-// scratch: 3 * attn_scratch_elems(B, S, h, dh) bf16 elements for the attention-transposed operand copies.
-size_t attn_scratch_elems(int B, int S, int h, int dh);
-int k_attn_fwd_mfma(hipStream_t st, const void* qkv, void* o, float* lse, void* scratch, int B, int S, int h, int dh);
+// Causal attention on the matrix cores (bf16, head dim 64 or 128).  The backward call also fills Dbuf with rowsum(dO * O).
+int k_attn_fwd_mfma(hipStream_t st, const void* qkv, void* o, float* lse, int B, int S, int h, int dh);
 int k_attn_bwd_mfma(hipStream_t st, const void* qkv, const void* o, const float* lse, const void* dO, void* dqkv, float* Dbuf,
-                    void* scratch, int B, int S, int h, int dh,
+                    int B, int S, int h, int dh,
                     const float* rope_cos, const float* rope_sin);          // tables given: dq, dk come out w.r.t. the un-rotated q, k
 
 }  // namespace pp

@@ -170,7 +170,8 @@ int pp_get_launch_counts(pp_model* m, int64_t* matrix_core_calls, int64_t* plain
 
 /* Options for tests and profiling.  "force_plain": 0 = automatic (MFMA kernels when shapes allow), 1 = force the
  * plain (non-MFMA) kernels.  "dw_tn": 1 (default) = weight-gradient GEMMs read their token-major operands directly
- * (LDS transpose reads), 0 = through transposed copies and the NT kernel.  "time_gemm": 1 = bracket every GEMM launch of later pp_local_step calls with a pair
+ * (LDS transpose reads), 0 = through transposed copies and the NT kernel.  "fuse_rope": 1 (default) = the rotary embedding of
+ * q and k is applied in the q|k|v projection's epilogue (one rounding), 0 = as a separate pass over the stored projection.  "time_gemm": 1 = bracket every GEMM launch of later pp_local_step calls with a pair
  * of HIP events on the model's stream (host-side events only; no device memory), 0 = off; setting it resets the totals.
  * "gemm_variant" (process-wide, for tests and A/B timing only; m may be NULL; takes effect for launches issued after the
  * call returns, on any thread): 1 = direct-to-LDS MFMA GEMM (default), 0 = register-staged MFMA GEMM.

@@ -163,6 +163,7 @@ struct pp_model {
   float *sp = nullptr, *sm = nullptr, *sv = nullptr, *sg = nullptr;
   long step = 0;
   int force_plain = 0;
+  int fuse_rope = 1;      // rotary embedding inside the q | k | v projection's epilogue (0: separate pass, for A/B timing)
   int dw_tn = 1;          // weight-gradient GEMMs read token-major operands directly (0: via transposed copies, for A/B timing)
   int jac_mode = 0, jac_lo = 0, jac_hi = 0;          // ablation: FFN input Jacobian over the trainable slice (+ units jac_lo..jac_hi-1) only
   double flops_fwd = 0, flops_bwd = 0, flops_recompute = 0, adamw_bytes = 0;
@@ -340,6 +341,7 @@ extern "C" int pp_set_option(pp_model* m, const char* key, int64_t value) {
   if (!m || !key) return fail(PP_EINVAL, "pp_set_option: NULL");
   if (!strcmp(key, "force_plain")) { m->force_plain = value != 0; return PP_OK; }
   if (!strcmp(key, "dw_tn")) { m->dw_tn = value != 0; return PP_OK; }
+  if (!strcmp(key, "fuse_rope")) { m->fuse_rope = value != 0; return PP_OK; }
   if (!strcmp(key, "gemm_variant")) { gemm_set_variant((int)value); return PP_OK; }
   if (!strcmp(key, "time_gemm")) {
     if (hipStreamSynchronize(m->st) != hipSuccess) return fail(PP_EHIP, "pp_set_option: stream sync failed");
@@ -522,6 +524,16 @@ static bool gemm_swiglu(pp_model* m, const void* X, const void* Wgu, void* gu, v
   return true;
 }
 
+// q | k | v projection with the rotary embedding of q and k applied in the GEMM's epilogue; false = not launched (shape or path)
+static bool gemm_qkv_rope(pp_model* m, const void* X, const void* Wqkv, void* qkv, int T, int d, int dh, int S, const float* cosb, const float* sinb) {
+  if (m->cfg.dtype != PP_BF16 || m->force_plain || !m->fuse_rope) return false;
+  GemmTimer timer(m, 2.0 * T * (3.0 * d) * d);
+  if (k_gemm_qkv_rope_mfma(m->st, X, d, Wqkv, d, qkv, T, d, dh, d, S, cosb, sinb) != 0) { timer.cancel(); return false; }
+  if (m->flop_acc) *m->flop_acc += 2.0 * T * (3.0 * d) * d;
+  m->n_mfma++;
+  return true;
+}
+
 // dA = G Wd_rows^T with the SwiGLU backward formed in the epilogue (dA itself is never stored); false = not launched
 static bool gemm_swiglu_bwd(pp_model* m, const void* G, const void* Wd_rows, const void* gu_c0, void* dgu_c0, int T, int nc, int F, int d) {
   if (m->cfg.dtype != PP_BF16 || m->force_plain) return false;
@@ -649,8 +661,10 @@ extern "C" int pp_local_step(pp_model* m, const int32_t* tokens_dev, const int32
     const int64_t lb = ly.layer0 + l * ly.layer_stride, sb = ly.sh_layer0 + l * ly.sh_layer_stride;
     void* x = act(l, w.a_x);
     k_rmsnorm_fwd(st, dt, x, canon(lb + ly.o_attn_norm), act(l, w.a_n1), (float*)act(l, w.a_rstd1), T, d, c.rms_eps);
-    gemm_nt(m, act(l, w.a_n1), d, canon(lb + ly.o_wqkv), d, act(l, w.a_qkv), 3 * d, T, 3 * d, d);
-    k_rope(st, dt, act(l, w.a_qkv), cosb, sinb, B, S, h, dh, 0);
+    if (!gemm_qkv_rope(m, act(l, w.a_n1), canon(lb + ly.o_wqkv), act(l, w.a_qkv), T, d, dh, S, cosb, sinb)) {
+      gemm_nt(m, act(l, w.a_n1), d, canon(lb + ly.o_wqkv), d, act(l, w.a_qkv), 3 * d, T, 3 * d, d);
+      k_rope(st, dt, act(l, w.a_qkv), cosb, sinb, B, S, h, dh, 0);
+    }
     attn_fwd(m, act(l, w.a_qkv), act(l, w.a_o), (float*)act(l, w.a_lse), B, S);
     gemm_nt(m, act(l, w.a_o), d, canon(lb + ly.o_wo), d, act(l, w.a_xm), d, T, d, d, EPI_ADD_RES, x);
     k_rmsnorm_fwd(st, dt, act(l, w.a_xm), canon(lb + ly.o_ffn_norm), act(l, w.a_n2), (float*)act(l, w.a_rstd2), T, d, c.rms_eps);

@@ -194,7 +194,10 @@ static_assert(BM == 256 && BN == 256, "unit geometry assumes 256-row panels");
 template <int EPI, bool OUT_F32>
 __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ B, int ldb,
                                                                void* Cv, int ldc, int M, int N, int Ksplit, const bf16_t* __restrict__ R,
-                                                               int tiles_m, int tiles_n, int ldc2) {
+                                                               int tiles_m, int tiles_n, int ldc2,
+                                                               const float* __restrict__ aux0, const float* __restrict__ aux1, int aux_n, int aux_s) {
+  // EPI_ROPE only: ldc2 = head dim, aux0 / aux1 = cos / sin tables [aux_s x head dim / 2], aux_n = number of leading output
+  // columns that are rotated (q and k), aux_s = sequence length (position of row t is t % aux_s)
   extern __shared__ u32x4 lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -232,6 +235,15 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
         // B = [W_g; W_u]): a wave's 64 output columns then hold gate and up of 32 units in matching registers
         const int unit = min(tn * (BN / 2) + (row >> 6) * 32 + (row & 31), N - 1);
         gB[i] = B + ((size_t)((row >> 5) & 1) * N + unit) * ldb + kbase + c * 8;
+      } else if constexpr (EPI == EPI_ROPE) {
+        // rotated columns: panel rows 64 w .. 64 w + 31 are 32 first-half elements i of one head, rows 64 w + 32 .. + 63 their
+        // partners i + dh/2, so that a lane's accumulators (i, j) and (i, j + 2) hold the two members of a rotary pair
+        int col = tn * BN + row;
+        if (tn * BN < aux_n) {
+          const int half = ldc2 >> 1, wph = half >> 5, wv = row >> 6, q = row & 63;
+          col = tn * BN + (wv / wph) * ldc2 + (wv % wph) * 32 + (q & 31) + (q >> 5) * half;
+        }
+        gB[i] = B + (size_t)min(col, N - 1) * ldb + kbase + c * 8;
       } else {
         gB[i] = B + (size_t)min(tn * BN + row, N - 1) * ldb + kbase + c * 8;
       }
@@ -413,7 +425,51 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
       // are written, 16-byte row chunks are read back so that 8 lanes cover one 128-byte row segment of C (and of the
       // residual).
       bf16_t* C = reinterpret_cast<bf16_t*>(Cv);
-      if constexpr (EPI == EPI_STORE) {
+      if (EPI == EPI_ROPE && n0 < aux_n) {
+        // ---- rotary epilogue (q and k columns).  acc[i][j] (j = 0, 1) holds elements p0 + 16 j + 4 (lane / 16) + r of one
+        // head's first half for output row m0 + wm*128 + 16 i + lane % 16, acc[i][j + 2] their partners dh/2 further on:
+        // (x1, x2) -> (x1 cos - x2 sin, x1 sin + x2 cos) with the angle of (row % aux_s, element), in fp32, rounded once.
+        // The two 64-byte segments go through the wave's LDS patch like the gate / up halves of the SwiGLU epilogue.
+        const int half = ldc2 >> 1, wph = half >> 5;
+        const int p0 = (wn % wph) * 32;                                  // first pair of this wave within its head
+        const int colbase = n0 + (wn / wph) * ldc2 + p0;                 // output column of that pair's first member
+#pragma unroll
+        for (int qt = 0; qt < 4; ++qt) {
+#pragma unroll
+          for (int ii = 0; ii < 2; ++ii) {
+            const int i = 2 * qt + ii, row = ii * 16 + l16;
+            const int pos = min(m0 + wm * 128 + 16 * i + l16, M - 1) % aux_s;
+            const float* cp = aux0 + (size_t)pos * half + p0 + 4 * lq;
+            const float* sp = aux1 + (size_t)pos * half + p0 + 4 * lq;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+              const float4 cs = *reinterpret_cast<const float4*>(cp + 16 * j), sn = *reinterpret_cast<const float4*>(sp + 16 * j);
+              const float cv[4] = {cs.x, cs.y, cs.z, cs.w}, sv[4] = {sn.x, sn.y, sn.z, sn.w};
+              float y1[4], y2[4];
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const float x1 = acc[i][j][e], x2 = acc[i][j + 2][e];
+                y1[e] = x1 * cv[e] - x2 * sv[e];
+                y2[e] = x1 * sv[e] + x2 * cv[e];
+              }
+              uint2 w1, w2;
+              w1.x = f32x2_to_bf16x2(y1[0], y1[1]); w1.y = f32x2_to_bf16x2(y1[2], y1[3]);
+              w2.x = f32x2_to_bf16x2(y2[0], y2[1]); w2.y = f32x2_to_bf16x2(y2[2], y2[3]);
+              const int pc = 2 * j + (lq >> 1);
+              char* rowp = wbase + row * 256 + (lq & 1) * 8;
+              *reinterpret_cast<uint2*>(rowp + (((0 + pc) ^ (row & 15)) << 4)) = w1;
+              *reinterpret_cast<uint2*>(rowp + (((4 + pc) ^ (row & 15)) << 4)) = w2;
+            }
+          }
+#pragma unroll
+          for (int it = 0; it < 4; ++it) {          // 8 pieces per row (4 of each half), 8 rows per wave instruction
+            const int row = 8 * it + (lane >> 3), pc = lane & 7;
+            const uint4 v = *reinterpret_cast<const uint4*>(wbase + row * 256 + ((pc ^ (row & 15)) << 4));
+            const int grow = m0 + wm * 128 + qt * 32 + row, gcol = colbase + (pc & 3) * 8 + (pc >> 2) * half;
+            if (grow < M && gcol < N) *reinterpret_cast<uint4*>(C + (size_t)grow * ldc + gcol) = v;
+          }
+        }
+      } else if constexpr (EPI == EPI_STORE || EPI == EPI_ROPE) {
         // 64 rows x 128 bytes (bf16) at a time; chunk c of row r sits at c ^ ((r >> 1) & 7)
 #pragma unroll
         for (int hi = 0; hi < 2; ++hi) {
@@ -574,7 +630,7 @@ static int launch_dl(hipStream_t st, const void* A, int lda, const void* B, int 
   if (!opt_in(reinterpret_cast<const void*>(kern), DL_LDS_BYTES)) return 1;
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   dim3 grid(splits == 1 ? dl_grid_x(tiles_m * tiles_n) : tiles_m * tiles_n, splits);
-  kern<<<grid, 512, DL_LDS_BYTES, st>>>((const bf16_t*)A, lda, (const bf16_t*)B, ldb, C, ldc, M, N, Ksplit, (const bf16_t*)R, tiles_m, tiles_n, 0);
+  kern<<<grid, 512, DL_LDS_BYTES, st>>>((const bf16_t*)A, lda, (const bf16_t*)B, ldb, C, ldc, M, N, Ksplit, (const bf16_t*)R, tiles_m, tiles_n, 0, nullptr, nullptr, 0, 1);
   return 0;
 }
 
@@ -586,7 +642,7 @@ int k_gemm_swiglu_fwd_mfma(hipStream_t st, const void* X, int ldx, const void* W
   auto kern = gemm_nt_mfma_dl_kernel<EPI_SWIGLU, false>;
   if (!opt_in(reinterpret_cast<const void*>(kern), DL_LDS_BYTES)) return 1;
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (F + BN / 2 - 1) / (BN / 2);
-  kern<<<dim3(dl_grid_x(tiles_m * tiles_n), 1), 512, DL_LDS_BYTES, st>>>((const bf16_t*)X, ldx, (const bf16_t*)Wgu, ldw, gu, 2 * F, M, F, K, (const bf16_t*)a, tiles_m, tiles_n, F);
+  kern<<<dim3(dl_grid_x(tiles_m * tiles_n), 1), 512, DL_LDS_BYTES, st>>>((const bf16_t*)X, ldx, (const bf16_t*)Wgu, ldw, gu, 2 * F, M, F, K, (const bf16_t*)a, tiles_m, tiles_n, F, nullptr, nullptr, 0, 1);
   return 0;
 }
 
@@ -600,7 +656,21 @@ int k_gemm_swiglu_bwd_mfma(hipStream_t st, const void* G, int ldg, const void* W
   auto kern = gemm_nt_mfma_dl_kernel<EPI_SWIGLU_BWD, false>;
   if (!opt_in(reinterpret_cast<const void*>(kern), DL_LDS_BYTES)) return 1;
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-  kern<<<dim3(dl_grid_x(tiles_m * tiles_n), 1), 512, DL_LDS_BYTES, st>>>((const bf16_t*)G, ldg, (const bf16_t*)Wd_rows, ldw, dgu_c0, ld2f, M, N, K, (const bf16_t*)gu_c0, tiles_m, tiles_n, half);
+  kern<<<dim3(dl_grid_x(tiles_m * tiles_n), 1), 512, DL_LDS_BYTES, st>>>((const bf16_t*)G, ldg, (const bf16_t*)Wd_rows, ldw, dgu_c0, ld2f, M, N, K, (const bf16_t*)gu_c0, tiles_m, tiles_n, half, nullptr, nullptr, 0, 1);
+  return 0;
+}
+
+int k_gemm_qkv_rope_mfma(hipStream_t st, const void* X, int ldx, const void* Wqkv, int ldw, void* qkv, int M, int d, int dh, int K, int S,
+                         const float* rope_cos, const float* rope_sin) {
+  if (g_gemm_variant.load(std::memory_order_relaxed) != 1 || M < 1 || S < 1 || d < BN || d % BN || (dh != 64 && dh != 128 && dh != 256) || d % dh) return 1;
+  if (K < DL_BK || K % DL_BK || (ldx & 7) || (ldw & 7) || !rope_cos || !rope_sin) return 1;
+  if (((uintptr_t)X | (uintptr_t)Wqkv | (uintptr_t)qkv | (uintptr_t)rope_cos | (uintptr_t)rope_sin) & 15) return 1;
+  static LdsOptIn opt_in;
+  auto kern = gemm_nt_mfma_dl_kernel<EPI_ROPE, false>;
+  if (!opt_in(reinterpret_cast<const void*>(kern), DL_LDS_BYTES)) return 1;
+  const int N = 3 * d, tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
+  kern<<<dim3(dl_grid_x(tiles_m * tiles_n), 1), 512, DL_LDS_BYTES, st>>>((const bf16_t*)X, ldx, (const bf16_t*)Wqkv, ldw, qkv, N, M, N, K, nullptr, tiles_m, tiles_n, dh,
+                                                                         rope_cos, rope_sin, 2 * d, S);
   return 0;
 }
 

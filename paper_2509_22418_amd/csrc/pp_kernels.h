@@ -18,7 +18,7 @@ struct ShadowSeg {      // one trainable row block that also lives, transposed, 
   int32_t rows, cols, shadow_ld, tile_start;   // tile_start: first 64x64 tile index of this block in the batched launch
 };
 
-enum { EPI_STORE = 0, EPI_ADD_RES = 1, EPI_SWIGLU = 2, EPI_SWIGLU_BWD = 3 };          // the last two: only inside k_gemm_swiglu_*_mfma
+enum { EPI_STORE = 0, EPI_ADD_RES = 1, EPI_SWIGLU = 2, EPI_SWIGLU_BWD = 3, EPI_ROPE = 4 };          // the last three: only inside k_gemm_swiglu_*_mfma / k_gemm_qkv_rope_mfma
 
 void k_fill_f32(hipStream_t st, float* p, size_t n, float v);
 void k_rope_tables(hipStream_t st, float* cosb, float* sinb, int S, int dh, float base);
@@ -74,6 +74,11 @@ int k_gemm_swiglu_fwd_mfma(hipStream_t st, const void* X, int ldx, const void* W
 // dgu columns c0.. and F + c0.. from the product G Wd_rows^T (= dL/da for N hidden units) and the saved gate / up; see the definition
 int k_gemm_swiglu_bwd_mfma(hipStream_t st, const void* G, int ldg, const void* Wd_rows, int ldw, const void* gu_c0, void* dgu_c0, int ld2f, int half,
                            int M, int N, int K);
+// qkv[M x 3d] (ld 3d) = X [Wq; Wk; Wv]^T with the rotary embedding applied to the q and k columns in the epilogue (fp32, before
+// the one rounding to bf16): position of row t is t % S, tables [S x dh/2] fp32.  Needs d % 256 == 0 and dh in {64, 128, 256};
+// returns non-zero (nothing launched) otherwise, and the caller runs the plain projection followed by k_rope.
+int k_gemm_qkv_rope_mfma(hipStream_t st, const void* X, int ldx, const void* Wqkv, int ldw, void* qkv, int M, int d, int dh, int K, int S,
+                         const float* rope_cos, const float* rope_sin);
 int k_gemm_nt_mfma(hipStream_t st, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K,
                    int epi, const void* R, int out_f32, int splits, float* partial);
 // Weight-gradient form: C[M x N] fp32 (ldc) = A^T B with A [K x M] (lda), B [K x N] (ldb) row-major bf16 -- no transposed

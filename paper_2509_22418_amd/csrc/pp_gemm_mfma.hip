@@ -430,6 +430,11 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
         // head's first half for output row m0 + wm*128 + 16 i + lane % 16, acc[i][j + 2] their partners dh/2 further on:
         // (x1, x2) -> (x1 cos - x2 sin, x1 sin + x2 cos) with the angle of (row % aux_s, element), in fp32, rounded once.
         // The two 64-byte segments go through the wave's LDS patch like the gate / up halves of the SwiGLU epilogue.
+        // (the lane index is laundered through an empty asm so that the per-lane addresses below are formed here, once per
+        // tile, instead of being hoisted above the main loop, where every register is taken, and spilled)
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+        const int e16 = ln & 15, eq = ln >> 4;
         const int half = ldc2 >> 1, wph = half >> 5;
         const int p0 = (wn % wph) * 32;                                  // first pair of this wave within its head
         const int colbase = n0 + (wn / wph) * ldc2 + p0;                 // output column of that pair's first member
@@ -437,10 +442,10 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
         for (int qt = 0; qt < 4; ++qt) {
 #pragma unroll
           for (int ii = 0; ii < 2; ++ii) {
-            const int i = 2 * qt + ii, row = ii * 16 + l16;
-            const int pos = min(m0 + wm * 128 + 16 * i + l16, M - 1) % aux_s;
-            const float* cp = aux0 + (size_t)pos * half + p0 + 4 * lq;
-            const float* sp = aux1 + (size_t)pos * half + p0 + 4 * lq;
+            const int i = 2 * qt + ii, row = ii * 16 + e16;
+            const int pos = min(m0 + wm * 128 + 16 * i + e16, M - 1) % aux_s;
+            const float* cp = aux0 + (size_t)pos * half + p0 + 4 * eq;
+            const float* sp = aux1 + (size_t)pos * half + p0 + 4 * eq;
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
               const float4 cs = *reinterpret_cast<const float4*>(cp + 16 * j), sn = *reinterpret_cast<const float4*>(sp + 16 * j);
@@ -455,15 +460,15 @@ __global__ __launch_bounds__(512) void gemm_nt_mfma_dl_kernel(const bf16_t* __re
               uint2 w1, w2;
               w1.x = f32x2_to_bf16x2(y1[0], y1[1]); w1.y = f32x2_to_bf16x2(y1[2], y1[3]);
               w2.x = f32x2_to_bf16x2(y2[0], y2[1]); w2.y = f32x2_to_bf16x2(y2[2], y2[3]);
-              const int pc = 2 * j + (lq >> 1);
-              char* rowp = wbase + row * 256 + (lq & 1) * 8;
+              const int pc = 2 * j + (eq >> 1);
+              char* rowp = wbase + row * 256 + (eq & 1) * 8;
               *reinterpret_cast<uint2*>(rowp + (((0 + pc) ^ (row & 15)) << 4)) = w1;
               *reinterpret_cast<uint2*>(rowp + (((4 + pc) ^ (row & 15)) << 4)) = w2;
             }
           }
 #pragma unroll
           for (int it = 0; it < 4; ++it) {          // 8 pieces per row (4 of each half), 8 rows per wave instruction
-            const int row = 8 * it + (lane >> 3), pc = lane & 7;
+            const int row = 8 * it + (ln >> 3), pc = ln & 7;
             const uint4 v = *reinterpret_cast<const uint4*>(wbase + row * 256 + ((pc ^ (row & 15)) << 4));
             const int grow = m0 + wm * 128 + qt * 32 + row, gcol = colbase + (pc & 3) * 8 + (pc >> 2) * half;
             if (grow < M && gcol < N) *reinterpret_cast<uint4*>(C + (size_t)grow * ldc + gcol) = v;

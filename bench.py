@@ -46,6 +46,22 @@ def closed_form_flops(cfg, B, S, rho, detach=False):
     return fwd, bwd
 
 
+def closed_form_flops_paper_mask(cfg, B, S, mask):
+    """Executed matmul FLOPs for the paper's masks (Section "Parameter Slicing": an FFN slice of every layer plus every
+    non-MLP parameter, optionally with the Q/K/V projections restricted to a head range).  The embeddings are trainable, so
+    nothing of the backward is skipped: per layer the input-gradient GEMMs run over all slices and heads (6TdF + 8Td^2 + 8Pd)
+    and the weight-gradient GEMMs only over the trainable row blocks (Appendix "FLOPs calculation", rho_mlp and rho_attn)."""
+    assert mask["train_embed"] and mask["train_wo"] and mask["train_lm_head"]
+    T = B * S
+    d, L, F, V, h = cfg["d_model"], cfg["n_layers"], cfg["d_ff"], cfg["vocab"], cfg["n_heads"]
+    P = B * S * (S + 1) // 2
+    Fk = mask["ffn_hi"] - mask["ffn_lo"]
+    nhd = (mask["head_hi"] - mask["head_lo"]) * (d // h)
+    fwd = L * (8 * T * d * d + 4 * P * d + 6 * T * d * F) + 2 * T * d * V
+    bwd = 4 * T * d * V + L * (6 * T * d * Fk + 6 * T * d * F + 2 * T * d * d + 2 * T * d * d + 8 * P * d + 6 * T * d * nhd + 6 * T * d * d)
+    return fwd, bwd
+
+
 class PowerSampler:
     """Board power as the driver reports it (hwmon `power1_input`, microwatts) sampled every 20 ms from a thread while
     the timed steps run; `power1_cap` is the board's limit.  Reported because the matrix kernels of this path run
@@ -211,7 +227,9 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="1p3b", choices=["1p3b", "125m"])
-    ap.add_argument("--legs", default="all", help="'main' = only the headline mask; 'all' = also rho=1/8 and all-trainable")
+    ap.add_argument("--legs", default="all", choices=["main", "all", "paper"],
+                    help="'main' = only the headline mask; 'all' = also rho=1/8, all-trainable, recomputation, the detach ablation and the "
+                         "paper's own masks; 'paper' = headline + the paper's masks")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=1234)
     ap.add_argument("--set", action="append", default=[], metavar="KEY=INT",
@@ -259,13 +277,21 @@ def main():
         legs.append(("rho=1/%d+recompute" % n_slices, gen.ffn_slice_mask(cfg, 0, n_slices), 1.0 / n_slices, dict(cfg, recompute=1)))
         # the appendix's detach-all-but-k ablation (a different, cheaper gradient that the paper reports to diverge)
         legs.append(("rho=1/%d+detach-ablation" % n_slices, gen.ffn_slice_mask(cfg, 0, n_slices), 1.0 / n_slices, dict(cfg, detach_jacobian=1)))
+    if args.legs in ("all", "paper"):
+        # the paper's own masks in the paper's memory regime (Table 1: "1/4 mlps" and "1/4 mlps + 1/4 heads"; full activation
+        # recomputation, Experimental Setup): every non-MLP parameter trainable, so 0.5-0.8 B packed elements go through AdamW
+        legs.append(("paper:1/4 mlps+recompute", gen.paper_mlp_mask(cfg, 0, 4), None, dict(cfg, recompute=1)))
+        legs.append(("paper:1/4 mlps+1/4 heads+recompute", gen.paper_mlp_mask(cfg, 0, 4, slice_heads=True), None, dict(cfg, recompute=1)))
     results = {}
     outer_step = None
     for name, mask, rho, leg_cfg in legs:
         t1 = time.perf_counter()
         r = run_leg(torch, pp, gen, leg_cfg, weights, mask, batches, args.steps, args.warmup, time_gemm=True,
                     outer=(name == legs[0][0]), seed=args.seed, options=[(kv.split("=")[0], int(kv.split("=")[1])) for kv in args.set])
-        fwd, bwd = closed_form_flops(cfg, B, S, rho, detach=bool(leg_cfg.get("detach_jacobian")))
+        if rho is None:
+            fwd, bwd = closed_form_flops_paper_mask(cfg, B, S, mask)
+        else:
+            fwd, bwd = closed_form_flops(cfg, B, S, rho, detach=bool(leg_cfg.get("detach_jacobian")))
         ms = r["seconds"] / args.steps * 1e3
         executed = r["counters"]["flops_fwd"] + r["counters"]["flops_bwd"]
         results[name] = dict(

@@ -324,7 +324,8 @@ def main():
                     traffic_note="null on purpose: FETCH_SIZE / WRITE_SIZE sit between L2 and the fabric, so for a GEMM they count "
                                  "L2 fills served by the Infinity Cache as well (about 0.9 GB per launch on average against 0.13-0.27 GB "
                                  "of operands, profiles/hbm_traffic_1p3b_rho32_pmc.txt), not HBM bytes; for the HBM-bound kernels of "
-                                 "the step the same counters equal the algorithmic bytes within 1-2 %",
+                                 "the step the same counters equal the algorithmic bytes within 1-2 %; L2 hit rate of the GEMM instantiations 0.69-0.80 "
+                                 "(profiles/l2_lds_counters_1p3b_rho32_pmc.txt)",
                     avg_launch_ms=round(gemm_ms_launch, 4), launches_per_step=mr["gemm_launches_per_step"],
                     measured_in="a second pass of the same leg with an event pair around every GEMM launch "
                                 f"({mr['ms_per_step_with_gemm_events']} ms/step); the headline ms_per_step is the pass without events",

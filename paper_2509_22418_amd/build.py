@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpp_hip.so")
-SOURCES = ["pp_api.hip", "pp_kernels.hip", "pp_gemm_mfma.hip", "pp_gemm_tn.hip", "pp_attn_mfma.hip"]
+SOURCES = ["pp_api.hip", "pp_kernels.hip", "pp_gemm_mfma.hip", "pp_gemm_tn.hip", "pp_gemm_nt128.hip", "pp_attn_mfma.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -338,6 +338,7 @@ extern "C" void pp_free(pp_model* m) { delete m; }
 extern "C" int pp_set_option(pp_model* m, const char* key, int64_t value) {
   if (key && !strcmp(key, "gemm_variant")) { gemm_set_variant((int)value); return PP_OK; }          // process-wide, no model needed
   if (key && !strcmp(key, "gemm_persistent")) { gemm_set_persistent(value != 0); return PP_OK; }
+  if (key && !strcmp(key, "gemm_small_tiles")) { gemm_set_small_tiles(value != 0); return PP_OK; }
   if (!m || !key) return fail(PP_EINVAL, "pp_set_option: NULL");
   if (!strcmp(key, "force_plain")) { m->force_plain = value != 0; return PP_OK; }
   if (!strcmp(key, "dw_tn")) { m->dw_tn = value != 0; return PP_OK; }

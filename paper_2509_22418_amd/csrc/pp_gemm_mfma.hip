@@ -609,6 +609,8 @@ static std::atomic<int> g_gemm_variant{1};          // 0: register-staged kernel
 void gemm_set_variant(int v) { g_gemm_variant.store(v, std::memory_order_relaxed); }
 static std::atomic<int> g_gemm_persistent{1};       // 1: one workgroup per compute unit walks several tiles (see the kernel's tile walk)
 void gemm_set_persistent(int v) { g_gemm_persistent.store(v, std::memory_order_relaxed); }
+static std::atomic<int> g_gemm_small_tiles{1};      // 1: few-tile GEMMs go to the 128 x 128-tile kernel
+void gemm_set_small_tiles(int v) { g_gemm_small_tiles.store(v, std::memory_order_relaxed); }
 // One-time opt-in of a kernel to more than 64 KB of dynamic LDS; safe when several host threads launch concurrently.
 struct LdsOptIn {
   std::once_flag once;
@@ -703,6 +705,12 @@ int k_gemm_nt_mfma(hipStream_t st, const void* A, int lda, const void* B, int ld
     return launch<EPI_STORE, true>(st, A, lda, B, ldb, partial, N, M, N, Ksplit, nullptr, splits);
   }
   if (out_f32) return epi == EPI_STORE ? launch<EPI_STORE, true>(st, A, lda, B, ldb, C, ldc, M, N, Ksplit, nullptr, 1) : 1;
+  // Fewer than 1.5 tiles of 256 x 256 per compute unit (d_model 768: 96 tiles for 256 units): 128 x 128 tiles, two
+  // workgroups per unit, fill the chip better than one partial round of big tiles.
+  const long tiles256 = (long)((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+  if (tiles256 < 384 && g_gemm_small_tiles.load(std::memory_order_relaxed) && g_gemm_variant.load(std::memory_order_relaxed) == 1 &&
+      k_gemm_nt128_mfma(st, A, lda, B, ldb, C, ldc, M, N, K, epi, R) == 0)
+    return 0;
   if (epi == EPI_ADD_RES) return launch<EPI_ADD_RES, false>(st, A, lda, B, ldb, C, ldc, M, N, Ksplit, R, 1);
   return launch<EPI_STORE, false>(st, A, lda, B, ldb, C, ldc, M, N, Ksplit, nullptr, 1);
 }

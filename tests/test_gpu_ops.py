@@ -37,12 +37,14 @@ GEMM_CASES = [
 ]
 
 
-@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("variant", [0, 1, 2])
 @pytest.mark.parametrize("M,N,K,res,f32,splits", GEMM_CASES)
 def test_gemm_nt_matches_definition(M, N, K, res, f32, splits, variant):
-    """variant 0: register-staged MFMA kernel; 1: direct-to-LDS MFMA kernel."""
+    """variant 0: register-staged MFMA kernel; 1: default dispatch (these shapes have few tiles: the 128 x 128-tile kernel for
+    bf16 output, the direct-to-LDS 256 x 256 kernel for fp32 output); 2: direct-to-LDS 256 x 256 kernel throughout."""
     print(f"case gemm {M}x{N}x{K} res={res} f32={f32} splits={splits} variant={variant}", flush=True)
-    pp.pp_set_option(None, "gemm_variant", variant)
+    pp.pp_set_option(None, "gemm_variant", min(variant, 1))
+    pp.pp_set_option(None, "gemm_small_tiles", 0 if variant == 2 else 1)
     Ad, A = dev_bf16(rnd((M, K), 1))
     Bd, B = dev_bf16(rnd((N, K), 2))
     ref = A @ B.T
@@ -78,6 +80,7 @@ def test_gemm_with_more_tiles_than_compute_units_walks_tiles_identically(M, N, r
     K = 128
     print(f"case gemm tile walk {M}x{N}x{K} res={res}", flush=True)
     pp.pp_set_option(None, "gemm_variant", 1)
+    pp.pp_set_option(None, "gemm_small_tiles", 0)          # these tile counts would otherwise go to the 128 x 128-tile kernel
     Ad, A = dev_bf16(rnd((M, K), 11))
     Bd, B = dev_bf16(rnd((N, K), 12))
     ref = A @ B.T

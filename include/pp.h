@@ -178,8 +178,8 @@ int pp_get_launch_counts(pp_model* m, int64_t* matrix_core_calls, int64_t* plain
  * "gemm_persistent" (process-wide, same caveats; m may be NULL): 1 (default) = when a GEMM has more tiles than the GPU has compute
  * units, one workgroup per unit walks several tiles and requests its next tile's first operands before the current
  * tile's epilogue; 0 = one workgroup per tile.  Same results bit for bit.
- * "gemm_small_tiles" (process-wide, same caveats; m may be NULL): 1 (default) = GEMMs with fewer than 384 output tiles of
- * 256 x 256 (less than 1.5 per compute unit) run on the 128 x 128-tile kernel; 0 = always 256 x 256 tiles. */
+ * "gemm_small_tiles" (process-wide, same caveats; m may be NULL): 1 (default) = GEMMs with at most 128 output tiles of
+ * 256 x 256 (half a tile per compute unit) run on the 128 x 128-tile kernel; 0 = always 256 x 256 tiles. */
 int pp_set_option(pp_model* m, const char* key, int64_t value);
 
 /* Blocks until the stream is idle, then returns the summed duration (ms), matmul FLOPs and number of the GEMM

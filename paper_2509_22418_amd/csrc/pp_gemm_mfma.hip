@@ -705,10 +705,12 @@ int k_gemm_nt_mfma(hipStream_t st, const void* A, int lda, const void* B, int ld
     return launch<EPI_STORE, true>(st, A, lda, B, ldb, partial, N, M, N, Ksplit, nullptr, splits);
   }
   if (out_f32) return epi == EPI_STORE ? launch<EPI_STORE, true>(st, A, lda, B, ldb, C, ldc, M, N, Ksplit, nullptr, 1) : 1;
-  // Fewer than 1.5 tiles of 256 x 256 per compute unit (d_model 768: 96 tiles for 256 units): 128 x 128 tiles, two
-  // workgroups per unit, fill the chip better than one partial round of big tiles.
+  // At most half a tile of 256 x 256 per compute unit (d_model 768: 96 tiles for 256 units): 128 x 128 tiles, two
+  // workgroups per unit, fill the chip better than a partial round of big tiles.  Measured crossover (8192 x N, K = 2048):
+  // the small kernel is 6 % faster at 128 big tiles and 27 % slower at 160 -- its waves of 64 x 64 sustain about 1.0 PFLOP/s
+  // against 1.4-1.5 for the big kernel's 128 x 64, so from 5/8 of a round on the big tiles win.
   const long tiles256 = (long)((M + BM - 1) / BM) * ((N + BN - 1) / BN);
-  if (tiles256 < 384 && g_gemm_small_tiles.load(std::memory_order_relaxed) && g_gemm_variant.load(std::memory_order_relaxed) == 1 &&
+  if (tiles256 <= 128 && g_gemm_small_tiles.load(std::memory_order_relaxed) && g_gemm_variant.load(std::memory_order_relaxed) == 1 &&
       k_gemm_nt128_mfma(st, A, lda, B, ldb, C, ldc, M, N, K, epi, R) == 0)
     return 0;
   if (epi == EPI_ADD_RES) return launch<EPI_ADD_RES, false>(st, A, lda, B, ldb, C, ldc, M, N, Ksplit, R, 1);

@@ -88,7 +88,7 @@ int k_gemm_tn_mfma(hipStream_t st, const void* A, int lda, int m_blk, long a_blk
                    int M, int N, int K, int splits, float* partial);
 // 128 x 128-tile variant for shapes with too few 256 x 256 tiles to fill the chip (bf16 out, EPI_STORE / EPI_ADD_RES)
 int k_gemm_nt128_mfma(hipStream_t st, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N, int K, int epi, const void* R);
-void gemm_set_small_tiles(int v);      // 1 (default): k_gemm_nt_mfma hands GEMMs with fewer than 1.5 tiles of 256 x 256 per compute unit to the 128 x 128 kernel
+void gemm_set_small_tiles(int v);      // 1 (default): k_gemm_nt_mfma hands GEMMs with at most 128 tiles of 256 x 256 (half a tile per compute unit) to the 128 x 128 kernel
 void gemm_set_variant(int v);          // 0: register-staged MFMA GEMM, 1: direct-to-LDS MFMA GEMM
 void gemm_set_persistent(int v);       // 1 (default): a workgroup per compute unit walks several tiles when there are more tiles than units
 // Causal attention on the matrix cores (bf16, head dim 64 or 128).  The backward call also fills Dbuf with rowsum(dO * O).

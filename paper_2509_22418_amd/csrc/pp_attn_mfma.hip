@@ -507,16 +507,19 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dq_kernel(const bf16_t* __res
 // overlap the other's matrix work -- and one barrier per tile is enough.
 // LDS: a ring of three tile sets (Q rows + dO rows of 64 queries; both roles read both tiles, tile i+1 is in flight while
 // tiles i and i-1 are in use) and two mailboxes: 128 KB at dh = 128.
-// The per-query statistics (log-sum-exp for the V-waves, D for the K-waves) go straight from global memory into
-// registers, one tile ahead.
+// The per-query statistics (log-sum-exp for the V-waves, D for the K-waves) travel with their tile: two 256-byte
+// direct-to-LDS loads per set (wave 0: the 64 log-sum-exps, wave 4: the 64 D values), read back as four floats per
+// accumulator row group when the tile is started -- no registers hold them in between, and no global load is waited
+// for inside an iteration.
 template <int DH, bool kwave>          // kwave false: V-wave (S, P, dV)   true: K-wave (dP, dS, dK)
 __device__ __forceinline__ void attn_bwd_dkv_part(u32x4* lds, const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO,
                                                   const float* __restrict__ lse, const float* __restrict__ Dbuf, bf16_t* __restrict__ dqkv,
-                                                  int S, int h, int stats_vec, int head, int b, int kblk, int lane, int wave,
+                                                  int S, int h, int head, int b, int kblk, int lane, int wave,
                                                   const float* __restrict__ cosb, const float* __restrict__ sinb) {
   constexpr int KS = DH / 16, CT = DH / 32, CPRK = DH / 8, NW = 8;
   constexpr int R_CH = 64 * CPRK, SET_CH = 2 * R_CH;          // a set = Q rows, then dO rows, of 64 queries
   constexpr int MAIL_CH = 2 * 4 * 2 * 64, MAIL0 = 3 * SET_CH;          // mailbox: [query group 2][key group 4][fragment 2][lane 64] chunks
+  constexpr int STAT0 = MAIL0 + 2 * MAIL_CH, STAT_CH = 2 * 16;          // per set: 64 floats of lse, then 64 floats of D
   const int d = h * DH, ld = 3 * d;
   const int l32 = lane & 31, lh = lane >> 5, kg = wave & 3;
   const uint32_t tr_off = tr_lane_off<CPRK>(lane);
@@ -524,7 +527,7 @@ __device__ __forceinline__ void attn_bwd_dkv_part(u32x4* lds, const bf16_t* __re
   const int key = kw0 + l32, keyc = min(key, S - 1);
   const bf16_t* base = qkv + (size_t)b * S * ld + (size_t)head * DH;
   const bf16_t* dob = dO + (size_t)b * S * d + (size_t)head * DH;
-  const float* statb = (kwave ? Dbuf : lse) + ((size_t)b * h + head) * S;
+  const float* statb = (kwave ? Dbuf : lse) + ((size_t)b * h + head) * S;          // wave 0 stages lse, wave 4 stages D
   const int t_first = k0 / 64, n_tiles = (S + 63) / 64 - t_first;
   const float scale = 1.0f / sqrtf((float)DH), sc2 = LOG2E * scale;
   const float st_mul = kwave ? -1.0f : -sqrtf((float)DH);
@@ -540,42 +543,20 @@ __device__ __forceinline__ void attn_bwd_dkv_part(u32x4* lds, const bf16_t* __re
   for (int c = 0; c < CT; ++c) zero16(oacc[c]);
 
   // sources as wave-uniform tile base + per-lane byte offset; rows past the end of the sequence repeat the last row
-  auto issue_set = [&](u32x4* set, int qq0) {
+  auto issue_set = [&](int slot, int qq0) {
+    u32x4* set = lds + slot * SET_CH;
     const int lim = S - 1 - qq0;
     Stage<64, CPRK, NW>::issue_u(set, wave, lane, base + (size_t)qq0 * ld, [=](int row, int c) { return (uint32_t)(min(row, lim) * ld + c * 8) * 2u; });
     Stage<64, CPRK, NW>::issue_u(set + R_CH, wave, lane, dob + (size_t)qq0 * d, [=](int row, int c) { return (uint32_t)(min(row, lim) * d + c * 8) * 2u; });
+    if (kg == 0)          // waves 0 and 4: the tile's 64 statistics, one float per lane (positions past the end repeat the last one)
+      __builtin_amdgcn_global_load_lds(PP_GPTR(statb + qq0 + min(lane, lim)), PP_LPTR(lds + STAT0 + slot * STAT_CH + (kwave ? 16 : 0)), 4, 0, 0);
   };
-  // statistics of this lane's 2 x 16 accumulator rows for the wave's next tile (rows past the end: any finite value)
-  float st[2][16];
-  auto load_stats = [&](int qq0) {
-    if (stats_vec && qq0 + 64 <= S) {          // wave-uniform
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const float4 v = *reinterpret_cast<const float4*>(statb + qq0 + mt * 32 + 8 * g + 4 * lh);
-          st[mt][4 * g] = v.x; st[mt][4 * g + 1] = v.y; st[mt][4 * g + 2] = v.z; st[mt][4 * g + 3] = v.w;
-        }
-    } else {          // ragged tail or unaligned rows: one base address, compile-time offsets, loads masked per lane
-      const float* sp = statb + qq0 + 4 * lh;
-      const int hi = S - (qq0 + 4 * lh);
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int o = mt * 32 + 8 * (r >> 2) + (r & 3);
-          st[mt][r] = o < hi ? sp[o] : 0.f;
-        }
-    }
-  };
-
-  issue_set(lds, t_first * 64);
-  load_stats(t_first * 64);          // first tile of either role
+  issue_set(0, t_first * 64);
   stage_sync();
 
   for (int it = 0; it <= n_tiles; ++it) {
     const int qv0 = (t_first + it) * 64;          // the V-waves' tile; the K-waves work on the one before it
-    if (it + 1 < n_tiles) issue_set(lds + ((it + 1) % 3) * SET_CH, qv0 + 64);          // ring slot of tile it-2, last read in iteration it-1
+    if (it + 1 < n_tiles) issue_set((it + 1) % 3, qv0 + 64);          // ring slot of tile it-2, last read in iteration it-1
     __builtin_amdgcn_sched_barrier(0);
     const int my_it = kwave ? it - 1 : it;          // index of the tile this wave works on now
     const int qq0 = (t_first + my_it) * 64;
@@ -587,10 +568,16 @@ __device__ __forceinline__ void attn_bwd_dkv_part(u32x4* lds, const bf16_t* __re
       // The accumulators start from the row statistics instead of zero, so the products come out as S - lse / scale
       // (V-wave) or dP - D (K-wave) and the statistics need no registers while the tile is worked on.
       f32x16 x[2];
+      {
+        const float* stp = reinterpret_cast<const float*>(lds + STAT0 + (my_it % 3) * STAT_CH + (kwave ? 16 : 0)) + 4 * lh;
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
+        for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) x[mt][r] = st[mt][r] * st_mul;
+          for (int g = 0; g < 4; ++g) {          // registers 4g .. 4g+3 are the queries 32 mt + 8 g + 4 lh .. + 3 of the tile
+            const float4 v = *reinterpret_cast<const float4*>(stp + mt * 32 + 8 * g);
+            x[mt][4 * g] = v.x * st_mul; x[mt][4 * g + 1] = v.y * st_mul; x[mt][4 * g + 2] = v.z * st_mul; x[mt][4 * g + 3] = v.w * st_mul;
+          }
+      }
       {          // both query groups at once: two independent accumulator chains
         __builtin_amdgcn_sched_barrier(0);
         bf16x8 rb[2][2];
@@ -670,7 +657,6 @@ __device__ __forceinline__ void attn_bwd_dkv_part(u32x4* lds, const bf16_t* __re
       }
     }
     __builtin_amdgcn_sched_barrier(0);
-    if (my_it + 1 < n_tiles) load_stats(qq0 + 64);          // for this wave's next tile; lands before the barrier below
     stage_sync();
   }
   if (key < S) {
@@ -694,7 +680,7 @@ __device__ __forceinline__ void attn_bwd_dkv_part(u32x4* lds, const bf16_t* __re
 template <int DH>
 __global__ __launch_bounds__(512, 2) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO,
                                                                const float* __restrict__ lse, const float* __restrict__ Dbuf,
-                                                               bf16_t* __restrict__ dqkv, int S, int h, int stats_vec, int n_pairs, int n_blk,
+                                                               bf16_t* __restrict__ dqkv, int S, int h, int n_pairs, int n_blk,
                                                                const float* __restrict__ cosb, const float* __restrict__ sinb) {
   extern __shared__ u32x4 lds[];
   int pair, comb;
@@ -705,8 +691,8 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dkv_kernel(const bf16_t* __re
   for (int part = 0; part < 2; ++part) {
     const int kblk = part == 0 ? comb : n_blk - 1 - comb;
     if (part == 1 && kblk == comb) break;
-    if (wave >= 4) attn_bwd_dkv_part<DH, true>(lds, qkv, dO, lse, Dbuf, dqkv, S, h, stats_vec, head, b, kblk, lane, wave, cosb, sinb);
-    else attn_bwd_dkv_part<DH, false>(lds, qkv, dO, lse, Dbuf, dqkv, S, h, stats_vec, head, b, kblk, lane, wave, cosb, sinb);
+    if (wave >= 4) attn_bwd_dkv_part<DH, true>(lds, qkv, dO, lse, Dbuf, dqkv, S, h, head, b, kblk, lane, wave, cosb, sinb);
+    else attn_bwd_dkv_part<DH, false>(lds, qkv, dO, lse, Dbuf, dqkv, S, h, head, b, kblk, lane, wave, cosb, sinb);
   }
 }
 
@@ -729,16 +715,15 @@ template <int DH>
 static int bwd_launch(hipStream_t st, const void* qkv, const void* o, const float* lse, const void* dO, void* dqkv, float* Dbuf,
                       int B, int S, int h, const float* cosb, const float* sinb) {
   constexpr int DQ_LDS = 2 * (2 * 64 * (DH / 8)) * 16;                                   // two stages of K rows + V rows
-  constexpr int DKV_LDS = (3 * (2 * 64 * (DH / 8)) + 2 * (2 * 4 * 2 * 64)) * 16;          // three sets of Q rows + dO rows, two P mailboxes
+  constexpr int DKV_LDS = (3 * (2 * 64 * (DH / 8)) + 2 * (2 * 4 * 2 * 64) + 3 * 32) * 16;          // three sets of Q rows + dO rows, two P mailboxes, three sets of statistics
   static bool ok = set_lds(attn_bwd_dq_kernel<DH>, DQ_LDS) && set_lds(attn_bwd_dkv_kernel<DH>, DKV_LDS);
   if (!ok) return 1;
   const int nb_kv = (S + 127) / 128, nb_dq = (S + 255) / 256;
-  const int stats_vec = (S % 4 == 0) && ((reinterpret_cast<uintptr_t>(lse) | reinterpret_cast<uintptr_t>(Dbuf)) & 15) == 0;          // 16-byte loads of lse / D
   // the dQ kernel also writes D = rowsum(dO * O), which the dK/dV kernel then reads
   attn_bwd_dq_kernel<DH><<<dim3(B * h * ((nb_dq + 1) / 2)), 512, DQ_LDS, st>>>((const bf16_t*)qkv, (const bf16_t*)o, (const bf16_t*)dO, lse, Dbuf, (bf16_t*)dqkv, S, h,
                                                                  B * h, nb_dq, cosb, sinb);
   attn_bwd_dkv_kernel<DH><<<dim3(B * h * ((nb_kv + 1) / 2)), 512, DKV_LDS, st>>>((const bf16_t*)qkv, (const bf16_t*)dO, lse, Dbuf,
-                                                      (bf16_t*)dqkv, S, h, stats_vec, B * h, nb_kv, cosb, sinb);
+                                                      (bf16_t*)dqkv, S, h, B * h, nb_kv, cosb, sinb);
   return 0;
 }
 

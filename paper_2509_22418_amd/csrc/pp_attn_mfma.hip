@@ -262,7 +262,10 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
             for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sacc[mt][r]);
         }
         tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64)) * sc2;
-        const float m_new = fmaxf(m_run, tmax);
+        // The reference point of the exponentials only has to keep them in range, it need not be the running maximum: it is
+        // moved (and the accumulators rescaled) only when a row's maximum has grown by more than 2^8 since it was set, so that
+        // p <= 256 and, once the first tiles are past, the 16 CT rescaling multiplies are skipped in nearly every tile.
+        const float m_new = tmax > m_run + 8.0f ? tmax : m_run;
         const float m_use = (m_new == -INFINITY) ? 0.f : m_new;          // whole row masked so far (only for padded queries)
         const float alpha = fast_exp2(m_run - m_use);
         float psum = 0.f;

@@ -773,7 +773,11 @@ extern "C" int pp_local_step(pp_model* m, const int32_t* tokens_dev, const int32
         k_rmsnorm_bwd(st, dt, dn, act(l, w.a_x), (float*)act(l, w.a_rstd1), canon(lb + ly.o_attn_norm), dx, dx, T, d);     // dx := dL/dx_l
         if (l == 0) reached_bottom = true;
       }
-      if (reached_bottom && mk.emb) k_embed_grad(st, dt, tokens_dev, dx, g + find_seg(m, TK_EMBED, -1)->packed_off, T, d, V);
+      if (reached_bottom && mk.emb) {
+        // the dL/da block is idle by now (the last layer's backward is done): room for the position index
+        const bool fits = ((size_t)T + 2 * (size_t)V) * 4 <= (size_t)T * F * esize(m->cfg);
+        k_embed_grad(st, dt, tokens_dev, dx, g + find_seg(m, TK_EMBED, -1)->packed_off, T, d, V, fits ? (int32_t*)(m->wsp + w.dA) : nullptr);
+      }
     }
   }
   m->flop_acc = nullptr;

@@ -58,7 +58,7 @@ void k_attn_D(hipStream_t st, int dtype, const void* o, const void* dO, float* D
 void k_attn_bwd_plain(hipStream_t st, int dtype, const void* qkv, const void* o, const float* lse, const void* dO, void* dqkv,
                       float* Dbuf, int B, int S, int h, int dh);
 
-void k_embed_grad(hipStream_t st, int dtype, const int32_t* tok, const void* dx, float* gE, int T, int d, int V);
+void k_embed_grad(hipStream_t st, int dtype, const int32_t* tok, const void* dx, float* gE, int T, int d, int V, int32_t* scratch);
 
 void k_pack_master(hipStream_t st, int dtype, const void* params, const RowInfo* rows, float* p, int n_rows, int d);
 void k_adamw(hipStream_t st, int dtype, void* params, const RowInfo* rows, float* p, float* m, float* v, const float* g,

@@ -857,8 +857,91 @@ __global__ void embed_grad_kernel(const int32_t* __restrict__ tok, const T* __re
     }
   }
 }
-void k_embed_grad(hipStream_t st, int dtype, const int32_t* tok, const void* dx, float* gE, int T_, int d, int V) {
-  PP_DISPATCH(dtype, embed_grad_kernel<T><<<V, 256, 0, st>>>(tok, (const T*)dx, gE, T_, d));
+// The same sums in the same order without every row scanning every token: positions are ranked by (token, position) --
+// one thread per position counts the positions with a smaller token and the earlier ones with its own token, T^2 / 2
+// comparisons from LDS -- which yields the position list of every token, in position order, as a segment of one array.
+// idx: [T] sorted positions, then [V] segment starts, then [V] segment lengths (lengths zeroed beforehand).
+__global__ __launch_bounds__(64) void embed_rank_kernel(const int32_t* __restrict__ tok, int32_t* __restrict__ idx, int T_, int V) {
+  __shared__ int32_t chunk[1024];
+  const int t = blockIdx.x * 64 + threadIdx.x;
+  const int my = t < T_ ? tok[t] : -1;
+  int less = 0, eq_before = 0, eq_total = 0;
+  for (int t0 = 0; t0 < T_; t0 += 1024) {
+    __syncthreads();
+    for (int i = threadIdx.x; i < 1024; i += 64) chunk[i] = t0 + i < T_ ? tok[t0 + i] : 0x7fffffff;
+    __syncthreads();
+    const int n = min(1024, T_ - t0);
+    for (int i = 0; i < n; ++i) {
+      const int o = chunk[i];
+      less += o < my;
+      eq_total += o == my;
+      eq_before += (o == my) & (t0 + i < t);
+    }
+  }
+  if (t >= T_ || my < 0 || my >= V) return;          // tokens outside the vocabulary contribute nothing (as in the forward gather's clamp-free contract)
+  idx[less + eq_before] = t;
+  if (eq_before == 0) { idx[T_ + my] = less; idx[T_ + V + my] = eq_total; }
+}
+// One block per vocabulary row, 256 threads = 4 hit lanes x 64 column lanes.  Hit lane j sums the row's positions
+// j, j+4, j+8, ... (in that order) for 16-byte column pieces, four loads in flight; the four partial sums are then added in
+// the order ((0 + 1) + 2) + 3.  The order is fixed, so the result does not depend on scheduling; a frequent token (the
+// synthetic tokens are Zipf distributed: the commonest one takes a tenth of the positions) costs a quarter of its count in
+// dependent steps instead of all of it.
+template <class T>
+__global__ __launch_bounds__(256) void embed_grad_sorted_kernel(const int32_t* __restrict__ idx, const T* __restrict__ dx, float* __restrict__ gE, int T_, int d, int V) {
+  constexpr int VEC = 16 / sizeof(T);          // elements per 16-byte piece
+  __shared__ float part[3][64 * VEC];
+  const int v = blockIdx.x;
+  const int nh = idx[T_ + V + v], s0 = nh ? idx[T_ + v] : 0;
+  const int hl = threadIdx.x >> 6, cl = threadIdx.x & 63;
+  float* out = gE + (size_t)v * d;
+  for (int c0 = 0; c0 < d; c0 += 64 * VEC) {          // uniform trip count: the barriers below are reached by every thread
+    const int c = c0 + cl * VEC;
+    float acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+    if (c < d) {
+      int k = hl;
+      for (; k + 12 < nh; k += 16) {          // four independent loads in flight
+        uint4 w[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) w[u] = *reinterpret_cast<const uint4*>(dx + (size_t)idx[s0 + k + 4 * u] * d + c);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const T* pv = reinterpret_cast<const T*>(&w[u]);
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) acc[e] += to_f32(pv[e]);
+        }
+      }
+      for (; k < nh; k += 4) {
+        const uint4 w = *reinterpret_cast<const uint4*>(dx + (size_t)idx[s0 + k] * d + c);
+        const T* pv = reinterpret_cast<const T*>(&w);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] += to_f32(pv[e]);
+      }
+    }
+    __syncthreads();          // the previous piece's partials have been read
+    if (hl > 0) {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) part[hl - 1][cl * VEC + e] = acc[e];
+    }
+    __syncthreads();
+    if (hl == 0 && c < d) {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) out[c + e] = ((acc[e] + part[0][cl * VEC + e]) + part[1][cl * VEC + e]) + part[2][cl * VEC + e];
+    }
+  }
+}
+// scratch: (T + 2 V) ints of device memory that nothing else uses during the call, or nullptr (then every row scans the tokens)
+void k_embed_grad(hipStream_t st, int dtype, const int32_t* tok, const void* dx, float* gE, int T_, int d, int V, int32_t* scratch) {
+  const int vec = dtype == 0 ? 4 : 8;          // elements per 16 bytes (dtype 0 = float, else bf16)
+  if (!scratch || d % vec || (reinterpret_cast<uintptr_t>(dx) & 15)) {          // no room for the index, or rows that 16-byte loads cannot take
+    PP_DISPATCH(dtype, embed_grad_kernel<T><<<V, 256, 0, st>>>(tok, (const T*)dx, gE, T_, d));
+    return;
+  }
+  k_fill_f32(st, reinterpret_cast<float*>(scratch + T_ + V), (size_t)V, 0.f);          // segment lengths := 0 (all-zero bits)
+  embed_rank_kernel<<<cdiv(T_, 64), 64, 0, st>>>(tok, scratch, T_, V);
+  PP_DISPATCH(dtype, embed_grad_sorted_kernel<T><<<V, 256, 0, st>>>(scratch, (const T*)dx, gE, T_, d, V));
 }
 
 // ------------------------------------------------------------------------------------------ packed-subset kernels
